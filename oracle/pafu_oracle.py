@@ -1,0 +1,244 @@
+"""fp64 CPU oracle for the PaFu-KV chunk step: score -> select -> compact -> attention.
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, plain statement of what the
+hot path computes.  It shares no code with the HIP library, imports nothing from
+the product package, and must never be called from a product code path: only the
+tests, the smoke check and the benchmark's CPU-baseline leg may use it.
+
+Every function is the definition written out (none of the four stages is an
+approximation of something else), in float64, with NumPy matmul / sort as the
+only library steps.  There is no tiling, no online softmax and no fusion.
+
+Inputs are whatever values the device path sees, widened exactly: a bf16 tensor
+arrives here as float32/float64 values that are exactly representable in bf16.
+
+Pins (tests/test_oracle_*.py): every function below is pinned by closed forms,
+brute force on tiny inputs, invariants, or reduction to an independent library
+routine.  The paper prints no worked numeric example for any stage, so no pin
+is a printed value.
+
+Notation follows the paper: N heads, D head dim, L_B block length, k budget,
+SL salience score list, KV cache.  Layouts are token-major: Q/K/V `[tokens, N, D]`.
+"""
+
+from __future__ import annotations
+
+import math
+
+import numpy as np
+from scipy.special import erf as _erf
+
+__all__ = [
+    "smlp_score",
+    "select_topk",
+    "compact_kv",
+    "chunk_attention",
+    "step_single",
+    "RolloutState",
+    "rollout_step",
+]
+
+
+# --------------------------------------------------------------------------------------
+# Salience Estimation Head (S-MLP)
+# --------------------------------------------------------------------------------------
+def smlp_score(X, W1, b1, W2, b2, act: str = "silu") -> np.ndarray:
+    """Per-token salience score of the S-MLP.
+
+    Appendix A ("S-MLP"): two linear layers with a SiLU in between, then the mean
+    over the output dimension; Sec. 3.3 / 3.4: the head maps per-token features to
+    one scalar per token.
+
+    X  [T, F]      per-token features (the caller concatenates Q|K|V when the
+                   paper-form input is wanted)
+    W1 [M, F], b1 [M] or None      first linear layer, out-features x in-features
+    W2 [n_out, M], b2 [n_out] or None
+    act: "silu" (the paper's) or "gelu_erf" (exact erf GELU, the benchmark
+         description's fallback wording)
+    returns s [T] float64
+    """
+    X = np.asarray(X, dtype=np.float64)
+    W1 = np.asarray(W1, dtype=np.float64)
+    W2 = np.asarray(W2, dtype=np.float64)
+    T, F = X.shape
+    M = W1.shape[0]
+    n_out = W2.shape[0]
+    assert W1.shape == (M, F) and W2.shape == (n_out, M)
+    h = X @ W1.T
+    if b1 is not None:
+        h = h + np.asarray(b1, dtype=np.float64)[None, :]
+    if act == "silu":
+        a = h * (1.0 / (1.0 + np.exp(-h)))
+    elif act == "gelu_erf":
+        a = 0.5 * h * (1.0 + _erf(h / math.sqrt(2.0)))
+    else:
+        raise ValueError(act)
+    y = a @ W2.T
+    if b2 is not None:
+        y = y + np.asarray(b2, dtype=np.float64)[None, :]
+    return y.sum(axis=1) / float(n_out)
+
+
+# --------------------------------------------------------------------------------------
+# Top-k retention
+# --------------------------------------------------------------------------------------
+def select_topk(scores_f32, k: int) -> np.ndarray:
+    """Indices of the k most salient tokens, ascending.
+
+    Sec. 3.4 (inference paragraph) and Alg. 2: keep the top-k of the score list.
+    Total order used: higher score first; equal scores -> lower token index first;
+    -0.0 equals +0.0; NaN ranks below -inf.  k >= n keeps everything (eviction only
+    happens once the cache exceeds its budget).  The decision is taken on the fp32
+    score values exactly as given.
+
+    returns int32 [min(k, n)], sorted ascending.
+    """
+    s = np.asarray(scores_f32, dtype=np.float32)
+    assert s.ndim == 1
+    n = s.shape[0]
+    k = int(k)
+    assert k >= 0
+    if k >= n:
+        return np.arange(n, dtype=np.int32)
+    isnan = np.isnan(s)
+    val = s.astype(np.float64)
+    val = np.where(isnan, 0.0, val) + 0.0  # x + 0.0 turns -0.0 into +0.0
+    idx = np.arange(n)
+    # lexsort: last key is the primary one.  NaN last, then value descending, then index.
+    order = np.lexsort((idx, -val, isnan.astype(np.int8)))
+    keep = order[:k]
+    return np.sort(keep).astype(np.int32)
+
+
+# --------------------------------------------------------------------------------------
+# Cache update: Select(KV; ids), Select(SL; ids)
+# --------------------------------------------------------------------------------------
+def compact_kv(K, V, SL, ids):
+    """Alg. 2, cache update: the retained rows of K, V and of the score list, in
+    the order ids gives (bit copies; dtype preserved)."""
+    ids = np.asarray(ids, dtype=np.int64)
+    K = np.asarray(K)
+    V = np.asarray(V)
+    SL = np.asarray(SL)
+    return K[ids].copy(), V[ids].copy(), SL[ids].copy()
+
+
+# --------------------------------------------------------------------------------------
+# Attention of the chunk's queries over retained cache + chunk
+# --------------------------------------------------------------------------------------
+def chunk_attention(Q, Kc, Vc, Kn, Vn, block_len: int, scale: float | None = None,
+                    rows=None, return_P: bool = False):
+    """O = softmax(Q [Kc;Kn]^T / sqrt(D) + mask) [Vc;Vn]   per head.
+
+    Sec. 3.2: P = softmax(Q K^T / sqrt(D)); blocks of length L_B with
+    b(i) = floor(i / L_B).  Every retained cache key is visible to every chunk
+    query; chunk key j is visible to chunk query i iff b(j) <= b(i) (block-causal;
+    L_B >= chunk length means no mask, the paper's setting, App. A).
+
+    Q  [Lq, N, D]   chunk queries        Kn, Vn [Lc, N, D]  the chunk's own keys/values
+    Kc, Vc [n, N, D] retained cache (n may be 0)
+    rows: optional 1-D array of query indices to compute (others are not returned)
+    returns O [len(rows) or Lq, N, D] float64  (and P [N, rows, n+Lc] if return_P)
+    """
+    Q = np.asarray(Q, dtype=np.float64)
+    Kc = np.asarray(Kc, dtype=np.float64)
+    Vc = np.asarray(Vc, dtype=np.float64)
+    Kn = np.asarray(Kn, dtype=np.float64)
+    Vn = np.asarray(Vn, dtype=np.float64)
+    Lq, N, D = Q.shape
+    n = Kc.shape[0]
+    Lc = Kn.shape[0]
+    assert block_len >= 1
+    if scale is None:
+        scale = 1.0 / math.sqrt(D)
+    if rows is None:
+        rows = np.arange(Lq)
+    rows = np.asarray(rows, dtype=np.int64)
+    K_all = np.concatenate([Kc.reshape(n, N, D), Kn], axis=0)
+    V_all = np.concatenate([Vc.reshape(n, N, D), Vn], axis=0)
+    # visibility[i, j] for chunk keys
+    bq = rows // block_len
+    bk = np.arange(Lc) // block_len
+    vis_chunk = bk[None, :] <= bq[:, None]
+    vis = np.concatenate([np.ones((rows.shape[0], n), dtype=bool), vis_chunk], axis=1)
+    O = np.empty((rows.shape[0], N, D), dtype=np.float64)
+    P_all = np.empty((N, rows.shape[0], n + Lc), dtype=np.float64) if return_P else None
+    for h in range(N):
+        z = (Q[rows, h, :] @ K_all[:, h, :].T) * scale
+        z = np.where(vis, z, -np.inf)
+        m = z.max(axis=1, keepdims=True)
+        p = np.exp(z - m)
+        p = p / p.sum(axis=1, keepdims=True)
+        O[:, h, :] = p @ V_all[:, h, :]
+        if return_P:
+            P_all[h] = p
+    if return_P:
+        return O, P_all
+    return O
+
+
+# --------------------------------------------------------------------------------------
+# One chunk step
+# --------------------------------------------------------------------------------------
+def step_single(X_cache, X_chunk, W1, b1, W2, b2, K_cache, V_cache, Q, K_chunk, V_chunk,
+                k: int, block_len: int, act: str = "silu", forced_scores_f32=None):
+    """One step in SINGLE mode: score cached and new tokens, select the top-k cached
+    tokens on the fresh cache scores, compact, attend (Alg. 2 order of operations;
+    Sec. 3.4).
+
+    forced_scores_f32: optional fp32 [n + Lc] vector used for selection instead of
+    the oracle's own rounded scores (teacher-forced parity: the device's scores are
+    fed in so that select/compact/attention can be compared exactly).
+
+    returns dict(scores [n+Lc] f64, ids, K_kept, V_kept, SL_kept, O)
+    """
+    n = X_cache.shape[0]
+    s_cache = smlp_score(X_cache, W1, b1, W2, b2, act) if n else np.zeros(0)
+    s_chunk = smlp_score(X_chunk, W1, b1, W2, b2, act)
+    s = np.concatenate([s_cache, s_chunk])
+    s32 = s.astype(np.float32) if forced_scores_f32 is None else np.asarray(forced_scores_f32, np.float32)
+    ids = select_topk(s32[:n], k)
+    Kk, Vk, SLk = compact_kv(K_cache, V_cache, s32[:n], ids)
+    O = chunk_attention(Q, Kk, Vk, K_chunk, V_chunk, block_len)
+    return dict(scores=s, ids=ids, K_kept=Kk, V_kept=Vk, SL_kept=SLk, O=O)
+
+
+class RolloutState:
+    """Cache state between chunks: K, V [n, N, D], SL [n] fp32, all caller-visible."""
+
+    def __init__(self, N: int, D: int, kv_dtype=np.float32):
+        self.K = np.zeros((0, N, D), dtype=kv_dtype)
+        self.V = np.zeros((0, N, D), dtype=kv_dtype)
+        self.SL = np.zeros((0,), dtype=np.float32)
+
+    @property
+    def n(self) -> int:
+        return self.K.shape[0]
+
+    def copy(self) -> "RolloutState":
+        c = RolloutState.__new__(RolloutState)
+        c.K, c.V, c.SL = self.K.copy(), self.V.copy(), self.SL.copy()
+        return c
+
+
+def rollout_step(state: RolloutState, X_chunk, W1, b1, W2, b2, Q, K_chunk, V_chunk,
+                 k: int, block_len: int, act: str = "silu", forced_chunk_scores_f32=None):
+    """One chunk of a rollout (Sec. 3.4 inference paragraph; Alg. 2).
+
+    The chunk's scores join the stored ones after its step, so the next step's
+    top-k runs over retained + that chunk and old and new tokens compete; stored
+    scores are never refreshed.  Order: score the chunk; select on the stored SL;
+    compact; attend over retained + chunk; append chunk K/V and its scores.
+
+    returns dict(s_chunk f64, ids, O); mutates state.
+    """
+    s_chunk = smlp_score(X_chunk, W1, b1, W2, b2, act)
+    s32 = (s_chunk.astype(np.float32) if forced_chunk_scores_f32 is None
+           else np.asarray(forced_chunk_scores_f32, np.float32))
+    ids = select_topk(state.SL, k)
+    Kk, Vk, SLk = compact_kv(state.K, state.V, state.SL, ids)
+    O = chunk_attention(Q, Kk, Vk, K_chunk, V_chunk, block_len)
+    state.K = np.concatenate([Kk, np.asarray(K_chunk, dtype=Kk.dtype)], axis=0)
+    state.V = np.concatenate([Vk, np.asarray(V_chunk, dtype=Vk.dtype)], axis=0)
+    state.SL = np.concatenate([SLk, s32]).astype(np.float32)
+    return dict(s_chunk=s_chunk, ids=ids, O=O)
