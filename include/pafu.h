@@ -1,0 +1,179 @@
+/*
+ * pafu.h - C ABI of the PaFu-KV chunk-step library for AMD MI355X (gfx950).
+ *
+ * One autoregressive chunk step of the paper's inference procedure (Sec. 3.4,
+ * inference paragraph; Alg. 2): score tokens with the Salience Estimation Head,
+ * keep the top-k cached tokens, compact the KV cache to them, and attend from the
+ * chunk's queries over the retained cache plus the chunk itself.
+ *
+ * Conventions (all entry points)
+ *  - Every pointer is a DEVICE pointer unless the comment says "host".
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *    only enqueue work; they never synchronise and never allocate device memory.
+ *  - Tensors are token-major: Q/K/V/O are [tokens, N, D] with an explicit token
+ *    stride `ld_*` counted in ELEMENTS (so a slab with spare capacity works);
+ *    inside a token the N*D elements are contiguous.  Scores are fp32, indices int32.
+ *  - Device pointers must be 16-byte aligned and token strides multiples of 16 bytes.
+ *  - Outputs must not alias inputs.  Weights and inputs are borrowed for the call.
+ *  - Return value: PAFU_OK (0) = enqueued; a negative pafu_status = error, in which
+ *    case NOTHING was enqueued and no output is touched.
+ *  - A budget k larger than the cache is not an error: everything is kept
+ *    (eviction only happens once the cache exceeds its budget, Alg. 2).
+ */
+#ifndef PAFU_H_
+#define PAFU_H_
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum pafu_status {
+  PAFU_OK = 0,
+  PAFU_ERR_NULL = -1,      /* a required pointer is NULL */
+  PAFU_ERR_SHAPE = -2,     /* a size is negative / zero where it may not be / unsupported (D not 64 or 128) */
+  PAFU_ERR_DTYPE = -3,     /* dtype enum value not supported by this call */
+  PAFU_ERR_ALIGN = -4,     /* pointer not 16-byte aligned or stride not a multiple of 16 bytes */
+  PAFU_ERR_WORKSPACE = -5, /* workspace NULL or smaller than pafu_*_workspace_bytes() */
+  PAFU_ERR_ALIAS = -6,     /* an output buffer overlaps an input buffer */
+  PAFU_ERR_HIP = -7        /* a HIP call failed; see pafu_last_hip_error() */
+} pafu_status;
+
+typedef enum pafu_dtype { PAFU_BF16 = 0, PAFU_F32 = 1 } pafu_dtype;
+typedef enum pafu_act { PAFU_ACT_SILU = 0, PAFU_ACT_GELU_ERF = 1 } pafu_act;
+typedef enum pafu_mode { PAFU_MODE_SINGLE = 0, PAFU_MODE_ROLLOUT = 1 } pafu_mode;
+
+/* Text for a pafu_status (static storage, host). */
+const char* pafu_strerror(int status);
+/* hipError_t of the last failed HIP call made by this library on the calling thread (0 if none). */
+int pafu_last_hip_error(void);
+/* Library ABI version (increases when a signature changes). */
+int pafu_version(void);
+
+/* ------------------------------------------------------------------------------------------
+ * pafu_score - Salience Estimation Head (S-MLP), App. A "S-MLP"; Sec. 3.3-3.4.
+ *
+ *   s[t] = mean_o( W2 . act( W1 . x[t] + b1 ) + b2 )_o          act = SiLU (the paper's)
+ *
+ * x[t] is the concatenation along the feature axis of n_seg (1..3) segments of Fs features
+ * each: row t of x0, then of x1, then of x2 (the paper feeds [Q | K | V]); F = n_seg * Fs.
+ *   x0,x1,x2 : [T, Fs] rows with stride ld_x elements, dtype x_dtype (x1/x2 ignored beyond n_seg)
+ *   W1       : [M, F] row-major (out-features x in-features), SAME dtype as x
+ *   b1       : [M] fp32 or NULL (= 0)
+ *   W2       : [n_out, M] fp32 row-major;  b2 : [n_out] fp32 or NULL
+ *   out      : [T] fp32
+ *   workspace: pafu_score_workspace_bytes(M) bytes (holds the output-averaged second layer)
+ * bf16 inputs with F % 64 == 0 and M % 32 == 0 take the MFMA path (fp32 accumulate); anything
+ * else takes a plain fp32-FMA path.  T == 0 is a no-op.
+ */
+size_t pafu_score_workspace_bytes(int M);
+int pafu_score(void* stream, const void* x0, const void* x1, const void* x2, int n_seg, int T, int Fs,
+               long long ld_x, int x_dtype, const void* W1, const float* b1, const float* W2,
+               const float* b2, int M, int n_out, int act, float* out, void* workspace,
+               size_t workspace_bytes);
+
+/* ------------------------------------------------------------------------------------------
+ * pafu_select_topk - top-k retention, Sec. 3.4 inference paragraph; Alg. 2 (Top-k of the score list).
+ *
+ * Writes the indices of the min(k, n) highest scores in ASCENDING index order.  Total order:
+ * higher score first; equal scores -> lower token index first; -0.0 == +0.0; NaN below -inf.
+ * The result is a pure function of the score bits (no dependence on scheduling).
+ *   scores    : [n] fp32          out_ids : [min(k, n)] int32
+ *   out_count : device int32 receiving min(k, n), or NULL
+ *   workspace : pafu_select_workspace_bytes(n) bytes
+ * n == 0 or k == 0 writes no index (out_count still receives 0).
+ */
+size_t pafu_select_workspace_bytes(int n);
+int pafu_select_topk(void* stream, const float* scores, int n, int k, int* out_ids, int* out_count,
+                     void* workspace, size_t workspace_bytes);
+
+/* ------------------------------------------------------------------------------------------
+ * pafu_compact_kv - cache update KV <- Select(KV; ids), SL <- Select(SL; ids), Alg. 2.
+ *
+ *   K_out[r] = K[ids[r]],  V_out[r] = V[ids[r]],  SL_out[r] = SL[ids[r]]     r in [0, count)
+ * Bit copies.  Out of place (the caller ping-pongs two slabs).
+ *   K, V      : [n, N, D] dtype `dtype` (2- or 4-byte elements), token stride ld_in elements
+ *   SL/SL_out : [n] / [count] fp32, both NULL to skip the score list
+ *   ids       : [count] int32 (device); an id outside [0, n) leaves that output row untouched
+ *   K_out,V_out : [count, N, D], token stride ld_out elements
+ * count == 0 is a no-op.
+ */
+int pafu_compact_kv(void* stream, const void* K, const void* V, const float* SL, long long ld_in, int n,
+                    const int* ids, int count, int N, int D, int dtype, void* K_out, void* V_out,
+                    float* SL_out, long long ld_out);
+
+/* ------------------------------------------------------------------------------------------
+ * pafu_chunk_attention - attention of the chunk's queries over retained cache + chunk.
+ * Sec. 3.2 (P = softmax(Q K^T / sqrt(D)), block boundaries from L_B); App. A (L_B = chunk length).
+ *
+ *   O[i,h,:] = sum_j softmax_j( scale * q[i,h].k[j,h] + mask(i,j) ) v[j,h]
+ * keys j run over the n_kept retained rows (all visible) followed by the Lc chunk rows; chunk key j
+ * is visible to query i iff floor(j / block_len) <= floor(i / block_len).  The two key segments are
+ * read in place (no concatenation copy).
+ *   Q  : [Lq, N, D] bf16, stride ld_q      Kc,Vc : [n_kept, N, D] bf16, stride ld_c (may be NULL if n_kept == 0)
+ *   Kn,Vn : [Lc, N, D] bf16, stride ld_n   O : [Lq, N, D] of out_dtype (bf16 or fp32), stride ld_o
+ *   softmax_scale <= 0 means 1/sqrt(D).    D must be 64 or 128.  Lq >= 1, Lc >= 1, block_len >= 1.
+ *   Query i is chunk token i (Lq <= Lc on this path).
+ *   workspace : pafu_attention_workspace_bytes(...) bytes (may be 0 -> NULL allowed)
+ */
+size_t pafu_attention_workspace_bytes(int Lq, int N, int D);
+int pafu_chunk_attention(void* stream, const void* Q, int Lq, const void* Kc, const void* Vc, int n_kept,
+                         const void* Kn, const void* Vn, int Lc, int N, int D, long long ld_q,
+                         long long ld_c, long long ld_n, long long ld_o, int block_len,
+                         float softmax_scale, void* O, int out_dtype, void* workspace,
+                         size_t workspace_bytes);
+
+/* ------------------------------------------------------------------------------------------
+ * pafu_step - one chunk step of one layer on one stream, Alg. 2; Sec. 3.4.
+ *
+ * SINGLE : scores the n cached tokens and the Lc chunk tokens (scores[0:n], scores[n:n+Lc]),
+ *          selects the top-k of the fresh cache scores, compacts K/V/SL into the output slab,
+ *          attends over the n_kept = min(k, n) retained rows + the chunk.
+ * ROLLOUT: scores only the chunk; selects on the STORED list SL_in (never refreshed); compacts into
+ *          the output slab rows [0, n_kept); attends; then appends the chunk's K/V rows and scores at
+ *          rows [n_kept, n_kept + Lc) of the output slab.  The caller swaps slabs for the next chunk,
+ *          whose cache size is n_kept + Lc, so old and new tokens compete at the next selection.
+ * All K/V tensors are bf16.  Feature tensors are x_dtype.
+ */
+typedef struct pafu_step_args {
+  int mode;            /* pafu_mode */
+  int N, D;            /* heads, head dim */
+  int n;               /* cached tokens on entry */
+  int Lc;              /* chunk tokens (= queries) */
+  int k;               /* budget */
+  int block_len;       /* L_B */
+  int M, n_out, act;   /* S-MLP hidden width, outputs, pafu_act */
+  int n_seg, Fs;       /* feature segments and width of each */
+  int x_dtype;         /* pafu_dtype of features and W1 */
+  int out_dtype;       /* pafu_dtype of O */
+  float softmax_scale; /* <= 0 -> 1/sqrt(D) */
+  long long ld_x;      /* feature row stride (elements) */
+  long long ld_cache;  /* token stride of K_cache/V_cache (elements) */
+  long long ld_out;    /* token stride of K_out/V_out */
+  long long ld_chunk;  /* token stride of Q, K_chunk, V_chunk */
+  long long ld_o;      /* token stride of O */
+  /* features: SINGLE scores x_cache* (n rows) and x_chunk* (Lc rows); ROLLOUT only x_chunk* */
+  const void* x_cache[3];
+  const void* x_chunk[3];
+  const void* W1; const float* b1; const float* W2; const float* b2;
+  const void* K_cache; const void* V_cache; /* [n, N, D] bf16 */
+  const float* SL_in;                       /* [n] stored scores (ROLLOUT) */
+  const void* Q; const void* K_chunk; const void* V_chunk; /* [Lc, N, D] bf16 */
+  float* scores;       /* SINGLE: [n + Lc] out.  ROLLOUT: unused (may be NULL) */
+  int* ids;            /* [min(k, n)] out */
+  void* K_out; void* V_out; /* [min(k,n) (+ Lc in ROLLOUT), N, D] bf16 out */
+  float* SL_out;       /* [min(k,n) (+ Lc in ROLLOUT)] out */
+  void* O;             /* [Lc, N, D] out */
+  void* workspace; size_t workspace_bytes; /* >= pafu_step_workspace_bytes(args) */
+} pafu_step_args;
+
+size_t pafu_step_workspace_bytes(const pafu_step_args* args /* host */);
+int pafu_step(void* stream, const pafu_step_args* args /* host */);
+/* The same step for n_layers independent layers (args[l] is layer l's arguments), enqueued on one stream. */
+int pafu_step_layers(void* stream, const pafu_step_args* args /* host array */, int n_layers);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PAFU_H_ */

@@ -1,0 +1,280 @@
+// C ABI of libpafu: argument validation and the chunk-step driver (Alg. 2 of the paper).
+// Every entry point validates on the host first; an error return means nothing was enqueued.
+#include <math.h>
+
+#include "pafu_internal.h"
+
+namespace pafu {
+namespace {
+thread_local int g_last_hip_error = 0;
+}
+int record_hip_error(hipError_t e) {
+  g_last_hip_error = static_cast<int>(e);
+  return PAFU_ERR_HIP;
+}
+namespace {
+
+int dtype_bytes(int dtype) { return dtype == PAFU_BF16 ? 2 : (dtype == PAFU_F32 ? 4 : 0); }
+
+int check_score(const void* x0, const void* x1, const void* x2, int n_seg, int T, int Fs, long long ld_x, int x_dtype,
+                const void* W1, const float* W2, int M, int n_out, int act, const float* out, const void* ws,
+                size_t ws_bytes) {
+  if (T < 0 || Fs <= 0 || M <= 0 || n_out <= 0 || n_seg < 1 || n_seg > 3 || ld_x < Fs) return PAFU_ERR_SHAPE;
+  if (act != PAFU_ACT_SILU && act != PAFU_ACT_GELU_ERF) return PAFU_ERR_SHAPE;
+  const int eb = dtype_bytes(x_dtype);
+  if (eb == 0) return PAFU_ERR_DTYPE;
+  if (T == 0) return PAFU_OK;
+  if (!x0 || (n_seg > 1 && !x1) || (n_seg > 2 && !x2) || !W1 || !W2 || !out) return PAFU_ERR_NULL;
+  if (!aligned16(x0) || (n_seg > 1 && !aligned16(x1)) || (n_seg > 2 && !aligned16(x2)) || !aligned16(W1) ||
+      !aligned16(W2) || (ld_x * eb) % 16 != 0)
+    return PAFU_ERR_ALIGN;
+  if (n_out > 1 && (ws == nullptr || ws_bytes < pafu_score_workspace_bytes(M))) return PAFU_ERR_WORKSPACE;
+  return PAFU_OK;
+}
+
+int check_select(const float* scores, int n, int k, const int* out_ids) {
+  if (n < 0 || k < 0) return PAFU_ERR_SHAPE;
+  if (n > 0 && !scores) return PAFU_ERR_NULL;
+  if (n > 0 && k > 0 && !out_ids) return PAFU_ERR_NULL;
+  if (!aligned16(scores)) return PAFU_ERR_ALIGN;
+  return PAFU_OK;
+}
+
+int check_compact(const void* K, const void* V, const float* SL, long long ld_in, int n, const int* ids, int count,
+                  int N, int D, int dtype, void* K_out, void* V_out, float* SL_out, long long ld_out) {
+  if (n < 0 || count < 0 || N <= 0 || D <= 0 || count > n) return PAFU_ERR_SHAPE;
+  const int eb = dtype_bytes(dtype);
+  if (eb == 0) return PAFU_ERR_DTYPE;
+  const long long row = (long long)N * D;
+  if (ld_in < row || ld_out < row || (row * eb) % 4 != 0 || row * eb > (1ll << 30)) return PAFU_ERR_SHAPE;
+  if (count == 0) return PAFU_OK;
+  if (!K || !V || !ids || !K_out || !V_out) return PAFU_ERR_NULL;
+  if ((SL == nullptr) != (SL_out == nullptr)) return PAFU_ERR_NULL;
+  if (!aligned16(K) || !aligned16(V) || !aligned16(K_out) || !aligned16(V_out) || (ld_in * eb) % 16 != 0 ||
+      (ld_out * eb) % 16 != 0)
+    return PAFU_ERR_ALIGN;
+  const size_t in_bytes = (size_t)n * ld_in * eb, out_bytes = (size_t)count * ld_out * eb;
+  if (overlaps(K, in_bytes, K_out, out_bytes) || overlaps(K, in_bytes, V_out, out_bytes) ||
+      overlaps(V, in_bytes, K_out, out_bytes) || overlaps(V, in_bytes, V_out, out_bytes) ||
+      overlaps(K_out, out_bytes, V_out, out_bytes) ||
+      (SL && overlaps(SL, (size_t)n * 4, SL_out, (size_t)count * 4)))
+    return PAFU_ERR_ALIAS;
+  return PAFU_OK;
+}
+
+int check_attention(const void* Q, int Lq, const void* Kc, const void* Vc, int n_kept, const void* Kn, const void* Vn,
+                    int Lc, int N, int D, long long ld_q, long long ld_c, long long ld_n, long long ld_o,
+                    int block_len, const void* O, int out_dtype) {
+  if (Lq < 1 || Lc < 1 || n_kept < 0 || N < 1 || N > 65535 || block_len < 1 || Lq > Lc) return PAFU_ERR_SHAPE;
+  if (D != 64 && D != 128) return PAFU_ERR_SHAPE;
+  if ((long long)n_kept + Lc > 0x7fff0000ll) return PAFU_ERR_SHAPE;
+  const int ob = dtype_bytes(out_dtype);
+  if (ob == 0) return PAFU_ERR_DTYPE;
+  const long long row = (long long)N * D;
+  if (ld_q < row || ld_n < row || ld_o < row || (n_kept > 0 && ld_c < row)) return PAFU_ERR_SHAPE;
+  if (!Q || !Kn || !Vn || !O || (n_kept > 0 && (!Kc || !Vc))) return PAFU_ERR_NULL;
+  if (!aligned16(Q) || !aligned16(Kn) || !aligned16(Vn) || !aligned16(O) || !aligned16(Kc) || !aligned16(Vc) ||
+      (ld_q * 2) % 16 != 0 || (ld_n * 2) % 16 != 0 || (ld_c * 2) % 16 != 0 || (ld_o * ob) % 16 != 0)
+    return PAFU_ERR_ALIGN;
+  const size_t o_bytes = (size_t)Lq * ld_o * ob;
+  if (overlaps(O, o_bytes, Q, (size_t)Lq * ld_q * 2) || overlaps(O, o_bytes, Kn, (size_t)Lc * ld_n * 2) ||
+      overlaps(O, o_bytes, Vn, (size_t)Lc * ld_n * 2) ||
+      (n_kept > 0 && (overlaps(O, o_bytes, Kc, (size_t)n_kept * ld_c * 2) ||
+                      overlaps(O, o_bytes, Vc, (size_t)n_kept * ld_c * 2))))
+    return PAFU_ERR_ALIAS;
+  return PAFU_OK;
+}
+
+size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Validates a whole step without enqueuing anything.
+int check_step(const pafu_step_args* a) {
+  if (!a) return PAFU_ERR_NULL;
+  if (a->mode != PAFU_MODE_SINGLE && a->mode != PAFU_MODE_ROLLOUT) return PAFU_ERR_SHAPE;
+  if (a->n < 0 || a->k < 0 || a->Lc < 1 || a->N < 1 || a->D < 1) return PAFU_ERR_SHAPE;
+  const int n_kept = a->k < a->n ? a->k : a->n;
+  const bool single = a->mode == PAFU_MODE_SINGLE;
+  if (a->workspace_bytes < pafu_step_workspace_bytes(a) || (a->workspace == nullptr && a->workspace_bytes > 0))
+    return PAFU_ERR_WORKSPACE;
+  if (pafu_step_workspace_bytes(a) > 0 && a->workspace == nullptr) return PAFU_ERR_WORKSPACE;
+  int rc;
+  float* chunk_scores = single ? (a->scores ? a->scores + a->n : nullptr) : (a->SL_out ? a->SL_out + n_kept : nullptr);
+  if (!chunk_scores) return PAFU_ERR_NULL;
+  if (single && a->n > 0) {
+    rc = check_score(a->x_cache[0], a->x_cache[1], a->x_cache[2], a->n_seg, a->n, a->Fs, a->ld_x, a->x_dtype, a->W1,
+                     a->W2, a->M, a->n_out, a->act, a->scores, a->workspace, a->workspace_bytes);
+    if (rc) return rc;
+  }
+  rc = check_score(a->x_chunk[0], a->x_chunk[1], a->x_chunk[2], a->n_seg, a->Lc, a->Fs, a->ld_x, a->x_dtype, a->W1,
+                   a->W2, a->M, a->n_out, a->act, chunk_scores, a->workspace, a->workspace_bytes);
+  if (rc) return rc;
+  const float* sel_scores = single ? a->scores : a->SL_in;
+  rc = check_select(sel_scores, a->n, a->k, a->ids);
+  if (rc) return rc;
+  if (a->n > 0 && !a->SL_out) return PAFU_ERR_NULL;
+  rc = check_compact(a->K_cache, a->V_cache, sel_scores, a->ld_cache, a->n, a->ids, n_kept, a->N, a->D, PAFU_BF16,
+                     a->K_out, a->V_out, a->SL_out, a->ld_out);
+  if (rc) return rc;
+  rc = check_attention(a->Q, a->Lc, a->K_out, a->V_out, n_kept, a->K_chunk, a->V_chunk, a->Lc, a->N, a->D, a->ld_chunk,
+                       a->ld_out, a->ld_chunk, a->ld_o, a->block_len, a->O, a->out_dtype);
+  if (rc) return rc;
+  if (!single) {
+    if (!a->K_out || !a->V_out) return PAFU_ERR_NULL;
+    if (!aligned16(a->K_out) || !aligned16(a->V_out) || (a->ld_out * 2) % 16 != 0) return PAFU_ERR_ALIGN;
+    if (a->ld_out < (long long)a->N * a->D) return PAFU_ERR_SHAPE;
+  }
+  return PAFU_OK;
+}
+
+int enqueue_step(hipStream_t st, const pafu_step_args* a) {
+  const int n_kept = a->k < a->n ? a->k : a->n;
+  const bool single = a->mode == PAFU_MODE_SINGLE;
+  const float scale = a->softmax_scale > 0.f ? a->softmax_scale : 1.0f / sqrtf((float)a->D);
+  int rc;
+  float* chunk_scores = single ? a->scores + a->n : a->SL_out + n_kept;
+  if (single && a->n > 0) {
+    // cache and chunk features that sit back to back are scored in one launch
+    const int eb = dtype_bytes(a->x_dtype);
+    bool contiguous = true;
+    for (int s = 0; s < a->n_seg; ++s)
+      contiguous = contiguous && static_cast<const char*>(a->x_chunk[s]) ==
+                                     static_cast<const char*>(a->x_cache[s]) + (long long)a->n * a->ld_x * eb;
+    if (contiguous) {
+      rc = launch_score(st, a->x_cache[0], a->x_cache[1], a->x_cache[2], a->n_seg, a->n + a->Lc, a->Fs, a->ld_x,
+                        a->x_dtype, a->W1, a->b1, a->W2, a->b2, a->M, a->n_out, a->act, a->scores, a->workspace);
+      if (rc) return rc;
+    } else {
+      rc = launch_score(st, a->x_cache[0], a->x_cache[1], a->x_cache[2], a->n_seg, a->n, a->Fs, a->ld_x, a->x_dtype,
+                        a->W1, a->b1, a->W2, a->b2, a->M, a->n_out, a->act, a->scores, a->workspace);
+      if (rc) return rc;
+      rc = launch_score(st, a->x_chunk[0], a->x_chunk[1], a->x_chunk[2], a->n_seg, a->Lc, a->Fs, a->ld_x, a->x_dtype,
+                        a->W1, a->b1, a->W2, a->b2, a->M, a->n_out, a->act, chunk_scores, a->workspace);
+      if (rc) return rc;
+    }
+  } else {
+    // SINGLE with an empty cache, or ROLLOUT (the chunk's scores land behind the retained ones in SL_out)
+    rc = launch_score(st, a->x_chunk[0], a->x_chunk[1], a->x_chunk[2], a->n_seg, a->Lc, a->Fs, a->ld_x, a->x_dtype,
+                      a->W1, a->b1, a->W2, a->b2, a->M, a->n_out, a->act, chunk_scores, a->workspace);
+    if (rc) return rc;
+  }
+  const float* sel_scores = single ? a->scores : a->SL_in;
+  if (a->n > 0) {
+    rc = launch_select(st, sel_scores, a->n, a->k, a->ids, nullptr, nullptr);
+    if (rc) return rc;
+    rc = launch_compact(st, a->K_cache, a->V_cache, sel_scores, a->ld_cache * 2, a->n, a->ids, n_kept,
+                        a->N * a->D * 2, a->K_out, a->V_out, a->SL_out, a->ld_out * 2);
+    if (rc) return rc;
+  }
+  rc = launch_attention(st, a->Q, a->Lc, a->K_out, a->V_out, n_kept, a->K_chunk, a->V_chunk, a->Lc, a->N, a->D,
+                        a->ld_chunk, a->ld_out, a->ld_chunk, a->ld_o, a->block_len, scale, a->O, a->out_dtype);
+  if (rc) return rc;
+  if (!single) {
+    char* ko = static_cast<char*>(a->K_out) + (long long)n_kept * a->ld_out * 2;
+    char* vo = static_cast<char*>(a->V_out) + (long long)n_kept * a->ld_out * 2;
+    rc = launch_append(st, a->K_chunk, a->V_chunk, nullptr, a->ld_chunk * 2, a->Lc, a->N * a->D * 2, ko, vo, nullptr,
+                       a->ld_out * 2);
+    if (rc) return rc;
+  }
+  return PAFU_OK;
+}
+
+}  // namespace
+}  // namespace pafu
+
+using namespace pafu;
+
+extern "C" {
+
+const char* pafu_strerror(int status) {
+  switch (status) {
+    case PAFU_OK: return "ok";
+    case PAFU_ERR_NULL: return "a required pointer is NULL";
+    case PAFU_ERR_SHAPE: return "invalid or unsupported size";
+    case PAFU_ERR_DTYPE: return "unsupported dtype";
+    case PAFU_ERR_ALIGN: return "pointer or stride not 16-byte aligned";
+    case PAFU_ERR_WORKSPACE: return "workspace missing or too small";
+    case PAFU_ERR_ALIAS: return "output overlaps an input";
+    case PAFU_ERR_HIP: return "a HIP call failed";
+    default: return "unknown status";
+  }
+}
+
+int pafu_last_hip_error(void) { return g_last_hip_error; }
+int pafu_version(void) { return 1; }
+
+size_t pafu_score_workspace_bytes(int M) { return M > 0 ? ((size_t)M + 1) * sizeof(float) : 0; }
+
+int pafu_score(void* stream, const void* x0, const void* x1, const void* x2, int n_seg, int T, int Fs, long long ld_x,
+               int x_dtype, const void* W1, const float* b1, const float* W2, const float* b2, int M, int n_out,
+               int act, float* out, void* workspace, size_t workspace_bytes) {
+  int rc = check_score(x0, x1, x2, n_seg, T, Fs, ld_x, x_dtype, W1, W2, M, n_out, act, out, workspace, workspace_bytes);
+  if (rc) return rc;
+  return launch_score(static_cast<hipStream_t>(stream), x0, x1, x2, n_seg, T, Fs, ld_x, x_dtype, W1, b1, W2, b2, M,
+                      n_out, act, out, workspace);
+}
+
+size_t pafu_select_workspace_bytes(int n) {
+  (void)n;
+  return 0;
+}
+
+int pafu_select_topk(void* stream, const float* scores, int n, int k, int* out_ids, int* out_count, void* workspace,
+                     size_t workspace_bytes) {
+  (void)workspace_bytes;
+  int rc = check_select(scores, n, k, out_ids);
+  if (rc) return rc;
+  return launch_select(static_cast<hipStream_t>(stream), scores, n, k, out_ids, out_count, workspace);
+}
+
+int pafu_compact_kv(void* stream, const void* K, const void* V, const float* SL, long long ld_in, int n, const int* ids,
+                    int count, int N, int D, int dtype, void* K_out, void* V_out, float* SL_out, long long ld_out) {
+  int rc = check_compact(K, V, SL, ld_in, n, ids, count, N, D, dtype, K_out, V_out, SL_out, ld_out);
+  if (rc) return rc;
+  const int eb = dtype_bytes(dtype);
+  return launch_compact(static_cast<hipStream_t>(stream), K, V, SL, ld_in * eb, n, ids, count, N * D * eb, K_out, V_out,
+                        SL_out, ld_out * eb);
+}
+
+size_t pafu_attention_workspace_bytes(int Lq, int N, int D) {
+  (void)Lq; (void)N; (void)D;
+  return 0;
+}
+
+int pafu_chunk_attention(void* stream, const void* Q, int Lq, const void* Kc, const void* Vc, int n_kept, const void* Kn,
+                         const void* Vn, int Lc, int N, int D, long long ld_q, long long ld_c, long long ld_n,
+                         long long ld_o, int block_len, float softmax_scale, void* O, int out_dtype, void* workspace,
+                         size_t workspace_bytes) {
+  (void)workspace; (void)workspace_bytes;
+  int rc = check_attention(Q, Lq, Kc, Vc, n_kept, Kn, Vn, Lc, N, D, ld_q, ld_c, ld_n, ld_o, block_len, O, out_dtype);
+  if (rc) return rc;
+  const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)D);
+  return launch_attention(static_cast<hipStream_t>(stream), Q, Lq, Kc, Vc, n_kept, Kn, Vn, Lc, N, D, ld_q, ld_c, ld_n,
+                          ld_o, block_len, scale, O, out_dtype);
+}
+
+size_t pafu_step_workspace_bytes(const pafu_step_args* a) {
+  if (!a) return 0;
+  return a->n_out > 1 ? align_up(pafu_score_workspace_bytes(a->M)) : 0;
+}
+
+int pafu_step(void* stream, const pafu_step_args* args) {
+  int rc = check_step(args);
+  if (rc) return rc;
+  return enqueue_step(static_cast<hipStream_t>(stream), args);
+}
+
+int pafu_step_layers(void* stream, const pafu_step_args* args, int n_layers) {
+  if (n_layers < 0) return PAFU_ERR_SHAPE;
+  if (n_layers > 0 && !args) return PAFU_ERR_NULL;
+  for (int l = 0; l < n_layers; ++l) {  // validate every layer before enqueuing any
+    int rc = check_step(&args[l]);
+    if (rc) return rc;
+  }
+  for (int l = 0; l < n_layers; ++l) {
+    int rc = enqueue_step(static_cast<hipStream_t>(stream), &args[l]);
+    if (rc) return rc;
+  }
+  return PAFU_OK;
+}
+
+}  // extern "C"

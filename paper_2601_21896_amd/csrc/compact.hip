@@ -1,0 +1,153 @@
+// Cache update: gather of the retained K/V rows (and their scores) into a contiguous cache.
+// Alg. 2 of the paper: KV <- Select(KV; ids), SL <- Select(SL; ids).
+//
+// Pure data movement, HBM-bound.  A retained row is N*D contiguous elements (3 KiB at 12x128 bf16),
+// so each wave copies whole rows with 16-byte lanes: every load and store is a full-line access and
+// evicted rows are never touched.  One wave moves one row of K and the same row of V per iteration,
+// with all of a row's loads issued before its stores so that several KiB per wave are in flight.
+#include "pafu_internal.h"
+
+namespace pafu {
+namespace {
+
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+
+constexpr int kCompactThreads = 256;
+constexpr int kWavesPerBlock = kCompactThreads / 64;
+constexpr int kMaxChunksPerLane = 12;  // rows up to 64*12*16 B = 12 KiB go through the unrolled path
+
+template <int CPL>  // 16-byte chunks per lane per row (row_bytes <= CPL*1024)
+__global__ __launch_bounds__(kCompactThreads) void compact_rows_kernel(
+    const char* __restrict__ K, const char* __restrict__ V, const float* __restrict__ SL, long long ld_in, int n,
+    const int* __restrict__ ids, int count, int chunks, char* __restrict__ Ko, char* __restrict__ Vo,
+    float* __restrict__ SLo, long long ld_out) {
+  const int lane = threadIdx.x & 63;
+  const int wave = blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+  const int n_waves = gridDim.x * kWavesPerBlock;
+  for (int r = wave; r < count; r += n_waves) {
+    const int id = ids[r];
+    if ((unsigned)id >= (unsigned)n) continue;  // invalid index: leave the row untouched
+    const u32x4* ks = reinterpret_cast<const u32x4*>(K + (long long)id * ld_in);
+    const u32x4* vs = reinterpret_cast<const u32x4*>(V + (long long)id * ld_in);
+    u32x4* kd = reinterpret_cast<u32x4*>(Ko + (long long)r * ld_out);
+    u32x4* vd = reinterpret_cast<u32x4*>(Vo + (long long)r * ld_out);
+    u32x4 kb[CPL], vb[CPL];
+#pragma unroll
+    for (int i = 0; i < CPL; ++i) {
+      const int c = lane + 64 * i;
+      if (c < chunks) {
+        kb[i] = __builtin_nontemporal_load(ks + c);
+        vb[i] = __builtin_nontemporal_load(vs + c);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < CPL; ++i) {
+      const int c = lane + 64 * i;
+      if (c < chunks) {
+        __builtin_nontemporal_store(kb[i], kd + c);
+        __builtin_nontemporal_store(vb[i], vd + c);
+      }
+    }
+    if (SL != nullptr && lane == 0) SLo[r] = SL[id];
+  }
+}
+
+// Rows longer than the unrolled path covers, or not a multiple of 16 bytes (then 4-byte words).
+template <typename W>
+__global__ __launch_bounds__(kCompactThreads) void compact_rows_generic_kernel(
+    const char* __restrict__ K, const char* __restrict__ V, const float* __restrict__ SL, long long ld_in, int n,
+    const int* __restrict__ ids, int count, int words, char* __restrict__ Ko, char* __restrict__ Vo,
+    float* __restrict__ SLo, long long ld_out) {
+  const int lane = threadIdx.x & 63;
+  const int wave = blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+  const int n_waves = gridDim.x * kWavesPerBlock;
+  for (int r = wave; r < count; r += n_waves) {
+    const int id = ids[r];
+    if ((unsigned)id >= (unsigned)n) continue;
+    const W* ks = reinterpret_cast<const W*>(K + (long long)id * ld_in);
+    const W* vs = reinterpret_cast<const W*>(V + (long long)id * ld_in);
+    W* kd = reinterpret_cast<W*>(Ko + (long long)r * ld_out);
+    W* vd = reinterpret_cast<W*>(Vo + (long long)r * ld_out);
+    for (int c = lane; c < words; c += 64) {
+      kd[c] = ks[c];
+      vd[c] = vs[c];
+    }
+    if (SL != nullptr && lane == 0) SLo[r] = SL[id];
+  }
+}
+
+// Contiguous row range copy (appending the chunk's rows to the compacted cache in a rollout).
+__global__ __launch_bounds__(kCompactThreads) void append_rows_kernel(
+    const char* __restrict__ K, const char* __restrict__ V, const float* __restrict__ S, long long ld_in, int rows,
+    int chunks, char* __restrict__ Ko, char* __restrict__ Vo, float* __restrict__ So, long long ld_out) {
+  const int lane = threadIdx.x & 63;
+  const int wave = blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+  const int n_waves = gridDim.x * kWavesPerBlock;
+  for (int r = wave; r < rows; r += n_waves) {
+    const u32x4* ks = reinterpret_cast<const u32x4*>(K + (long long)r * ld_in);
+    const u32x4* vs = reinterpret_cast<const u32x4*>(V + (long long)r * ld_in);
+    u32x4* kd = reinterpret_cast<u32x4*>(Ko + (long long)r * ld_out);
+    u32x4* vd = reinterpret_cast<u32x4*>(Vo + (long long)r * ld_out);
+    for (int c = lane; c < chunks; c += 64) {
+      kd[c] = ks[c];
+      vd[c] = vs[c];
+    }
+    if (S != nullptr && lane == 0) So[r] = S[r];
+  }
+}
+
+int grid_for_rows(int rows) {
+  // one row per wave per iteration; enough blocks to cover the chip several times over
+  long long blocks = ((long long)rows + kWavesPerBlock - 1) / kWavesPerBlock;
+  const long long cap = 256 * 16;
+  if (blocks > cap) blocks = cap;
+  if (blocks < 1) blocks = 1;
+  return (int)blocks;
+}
+
+}  // namespace
+
+int launch_compact(hipStream_t st, const void* K, const void* V, const float* SL, long long ld_in_bytes, int n,
+                   const int* ids, int count, int row_bytes, void* K_out, void* V_out, float* SL_out,
+                   long long ld_out_bytes) {
+  if (count <= 0) return PAFU_OK;
+  const dim3 grid(grid_for_rows(count)), block(kCompactThreads);
+  const char* k = static_cast<const char*>(K);
+  const char* v = static_cast<const char*>(V);
+  char* ko = static_cast<char*>(K_out);
+  char* vo = static_cast<char*>(V_out);
+  if (row_bytes % 16 == 0 && row_bytes <= kMaxChunksPerLane * 1024) {
+    const int chunks = row_bytes / 16;
+    const int cpl = (chunks + 63) / 64;
+#define PAFU_COMPACT_CASE(C)                                                                                  \
+  hipLaunchKernelGGL(compact_rows_kernel<C>, grid, block, 0, st, k, v, SL, ld_in_bytes, n, ids, count, chunks, \
+                     ko, vo, SL_out, ld_out_bytes)
+    if (cpl <= 1) PAFU_COMPACT_CASE(1);
+    else if (cpl <= 2) PAFU_COMPACT_CASE(2);
+    else if (cpl <= 3) PAFU_COMPACT_CASE(3);
+    else if (cpl <= 4) PAFU_COMPACT_CASE(4);
+    else if (cpl <= 6) PAFU_COMPACT_CASE(6);
+    else if (cpl <= 8) PAFU_COMPACT_CASE(8);
+    else if (cpl <= 10) PAFU_COMPACT_CASE(10);
+    else PAFU_COMPACT_CASE(12);
+#undef PAFU_COMPACT_CASE
+  } else if (row_bytes % 16 == 0) {
+    hipLaunchKernelGGL(compact_rows_generic_kernel<u32x4>, grid, block, 0, st, k, v, SL, ld_in_bytes, n, ids, count,
+                       row_bytes / 16, ko, vo, SL_out, ld_out_bytes);
+  } else {
+    hipLaunchKernelGGL(compact_rows_generic_kernel<unsigned int>, grid, block, 0, st, k, v, SL, ld_in_bytes, n, ids,
+                       count, row_bytes / 4, ko, vo, SL_out, ld_out_bytes);
+  }
+  return check_launch();
+}
+
+int launch_append(hipStream_t st, const void* K, const void* V, const float* S, long long ld_in_bytes, int rows,
+                  int row_bytes, void* K_out, void* V_out, float* S_out, long long ld_out_bytes) {
+  if (rows <= 0) return PAFU_OK;
+  hipLaunchKernelGGL(append_rows_kernel, dim3(grid_for_rows(rows)), dim3(kCompactThreads), 0, st,
+                     static_cast<const char*>(K), static_cast<const char*>(V), S, ld_in_bytes, rows, row_bytes / 16,
+                     static_cast<char*>(K_out), static_cast<char*>(V_out), S_out, ld_out_bytes);
+  return check_launch();
+}
+
+}  // namespace pafu

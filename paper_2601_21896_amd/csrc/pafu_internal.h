@@ -1,0 +1,39 @@
+// Internal helpers shared by the HIP translation units of libpafu (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "pafu.h"
+
+namespace pafu {
+
+// Records a failed HIP call for pafu_last_hip_error(); returns PAFU_ERR_HIP.
+int record_hip_error(hipError_t e);
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline int check_launch() {
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? PAFU_OK : record_hip_error(e);
+}
+
+inline bool overlaps(const void* a, size_t a_bytes, const void* b, size_t b_bytes) {
+  uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+  return a_bytes && b_bytes && a0 < b0 + b_bytes && b0 < a0 + a_bytes;
+}
+
+// Stage launchers (validated arguments only).
+int launch_compact(hipStream_t st, const void* K, const void* V, const float* SL, long long ld_in_bytes, int n,
+                   const int* ids, int count, int row_bytes, void* K_out, void* V_out, float* SL_out,
+                   long long ld_out_bytes);
+int launch_append(hipStream_t st, const void* K, const void* V, const float* S, long long ld_in_bytes, int rows,
+                  int row_bytes, void* K_out, void* V_out, float* S_out, long long ld_out_bytes);
+int launch_select(hipStream_t st, const float* scores, int n, int k, int* out_ids, int* out_count, void* ws);
+int launch_score(hipStream_t st, const void* x0, const void* x1, const void* x2, int n_seg, int T, int Fs,
+                 long long ld_x, int x_dtype, const void* W1, const float* b1, const float* W2, const float* b2,
+                 int M, int n_out, int act, float* out, void* ws);
+int launch_attention(hipStream_t st, const void* Q, int Lq, const void* Kc, const void* Vc, int n_kept,
+                     const void* Kn, const void* Vn, int Lc, int N, int D, long long ld_q, long long ld_c,
+                     long long ld_n, long long ld_o, int block_len, float scale, void* O, int out_dtype);
+
+}  // namespace pafu

@@ -1,0 +1,100 @@
+"""GPU parity of pafu_chunk_attention against the fp64 oracle (max-abs 2e-2, relative Frobenius 5e-3)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import pafu_oracle as orc
+from paper_2601_21896_amd import binding as B
+from paper_2601_21896_amd import workloads as wl
+from tests.gpu_util import ATTN_MAX_ABS, ATTN_REL_FRO, DEV, attn_errors, dev, host
+
+pytestmark = pytest.mark.gpu
+
+
+def _inputs(n, Lc, N, D, seed, q_gain=1.0):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    c = rng.uniform(0.5, 2.0, size=(N * D,)).astype(np.float32)
+    r = lambda rows, s=None: wl.round_to_bf16(
+        (rng.standard_normal((rows, N * D), dtype=np.float32) * (1.0 if s is None else s[None, :]))).reshape(rows, N, D)
+    Kc, Vc = r(n, c), r(n)
+    Q = wl.round_to_bf16(r(Lc) * np.float32(q_gain))
+    Kn, Vn = r(Lc, c), r(Lc)
+    return Q, Kc, Vc, Kn, Vn
+
+
+def _run(Q, Kc, Vc, Kn, Vn, L_B, out_dtype=torch.bfloat16, Lq=None):
+    Lq = Q.shape[0] if Lq is None else Lq
+    N, D = Q.shape[1], Q.shape[2]
+    n = Kc.shape[0]
+    O = torch.full((Lq + 2, N, D), 55.0, device=DEV, dtype=out_dtype)
+    dQ = dev(Q[:Lq], "bf16")
+    dKc = dev(Kc, "bf16") if n else None
+    dVc = dev(Vc, "bf16") if n else None
+    B.pafu_chunk_attention(dQ, dKc, dVc, n, dev(Kn, "bf16"), dev(Vn, "bf16"), L_B, O[:Lq])
+    torch.cuda.synchronize()
+    assert torch.all(O[Lq:] == 55.0)
+    return host(O[:Lq])
+
+
+@pytest.mark.parametrize("n,Lc,N,D,L_B", [
+    (128, 64, 2, 64, 64),        # C0 shapes after budget 50%
+    (128, 64, 2, 64, 16),
+    (128, 64, 2, 64, 1),         # causal inside the chunk
+    (0, 64, 2, 64, 64),          # first chunk: empty cache
+    (0, 40, 1, 128, 7),
+    (300, 200, 3, 128, 200),     # ragged query tile (200 = 128 + 72) and key tail (500 = 7*64 + 52)
+    (300, 200, 3, 128, 50),
+    (333, 130, 2, 128, 13),
+    (1, 1, 1, 128, 1),
+    (63, 129, 2, 64, 129),
+    (1000, 520, 2, 128, 130),
+])
+def test_attention_matches_oracle(n, Lc, N, D, L_B):
+    Q, Kc, Vc, Kn, Vn = _inputs(n, Lc, N, D, seed=n * 7 + Lc)
+    got = _run(Q, Kc, Vc, Kn, Vn, L_B)
+    want = orc.chunk_attention(Q, Kc, Vc, Kn, Vn, block_len=L_B)
+    max_abs, rel = attn_errors(got, want)
+    assert max_abs < ATTN_MAX_ABS and rel < ATTN_REL_FRO, (max_abs, rel)
+
+
+def test_attention_peaked_softmax_and_fp32_output():
+    # queries scaled x8: the softmax is peaked, |O| ~ 1, so the max-abs bound bites
+    n, Lc, N, D = 500, 192, 2, 128
+    Q, Kc, Vc, Kn, Vn = _inputs(n, Lc, N, D, seed=99, q_gain=8.0)
+    want = orc.chunk_attention(Q, Kc, Vc, Kn, Vn, block_len=64)
+    assert np.abs(want).max() > 0.5
+    for odt in (torch.bfloat16, torch.float32):
+        got = _run(Q, Kc, Vc, Kn, Vn, 64, out_dtype=odt)
+        max_abs, rel = attn_errors(got, want)
+        assert max_abs < ATTN_MAX_ABS and rel < ATTN_REL_FRO, (odt, max_abs, rel)
+
+
+def test_attention_large_key_offset_and_fewer_queries():
+    # a large common vector on every key shifts logits by a per-row constant: exercises the running max
+    n, Lc, N, D = 200, 100, 2, 128
+    Q, Kc, Vc, Kn, Vn = _inputs(n, Lc, N, D, seed=5)
+    shift = wl.round_to_bf16(np.full((1, N, D), 3.0, np.float32))
+    Kc2, Kn2 = wl.round_to_bf16(Kc + shift), wl.round_to_bf16(Kn + shift)
+    got = _run(Q, Kc2, Vc, Kn2, Vn, 25, Lq=70)
+    want = orc.chunk_attention(Q[:70], Kc2, Vc, Kn2, Vn, block_len=25)
+    max_abs, rel = attn_errors(got, want)
+    assert max_abs < ATTN_MAX_ABS and rel < ATTN_REL_FRO, (max_abs, rel)
+
+
+def test_attention_strided_slabs():
+    # cache rows live in a slab with spare capacity and a wider token stride
+    n, Lc, N, D = 150, 70, 2, 64
+    Q, Kc, Vc, Kn, Vn = _inputs(n, Lc, N, D, seed=17)
+    ld = N * D + 64
+    slabK = torch.zeros(n + 10, ld, device=DEV, dtype=torch.bfloat16)
+    slabV = torch.zeros(n + 10, ld, device=DEV, dtype=torch.bfloat16)
+    slabK[:n, : N * D] = dev(Kc, "bf16").view(n, N * D)
+    slabV[:n, : N * D] = dev(Vc, "bf16").view(n, N * D)
+    Kv = slabK.as_strided((n, N, D), (ld, D, 1))
+    Vv = slabV.as_strided((n, N, D), (ld, D, 1))
+    O = torch.empty(Lc, N, D, device=DEV, dtype=torch.bfloat16)
+    B.pafu_chunk_attention(dev(Q, "bf16"), Kv, Vv, n, dev(Kn, "bf16"), dev(Vn, "bf16"), 35, O)
+    torch.cuda.synchronize()
+    want = orc.chunk_attention(Q, Kc, Vc, Kn, Vn, block_len=35)
+    max_abs, rel = attn_errors(host(O), want)
+    assert max_abs < ATTN_MAX_ABS and rel < ATTN_REL_FRO, (max_abs, rel)

@@ -1,0 +1,121 @@
+"""The C-ABI library loads, exports every declared symbol, and rejects bad arguments on the host
+(no GPU needed: validation happens before any HIP call)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2601_21896_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "pafu.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pafu_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    lib = binding.library()
+    names = _declared_symbols()
+    assert set(names) == set(binding.SYMBOLS)
+    for name in names:
+        assert getattr(lib, name) is not None
+    assert binding.pafu_version() >= 1
+    assert binding.pafu_strerror(0) == "ok"
+    assert "NULL" in binding.pafu_strerror(-1)
+
+
+def test_workspace_queries():
+    assert binding.pafu_score_workspace_bytes(256) >= 257 * 4
+    assert binding.pafu_select_workspace_bytes(32760) >= 0
+    assert binding.pafu_attention_workspace_bytes(4680, 12, 128) >= 0
+
+
+A = 0x10000   # a fake, 16-byte aligned "device address": validation must fail before it is ever used
+
+
+def test_select_rejects_bad_arguments():
+    lib = binding.library()
+    assert lib.pafu_select_topk(None, None, 10, 3, A, None, None, 0) == -1       # NULL scores
+    assert lib.pafu_select_topk(None, A, -1, 3, A, None, None, 0) == -2          # n < 0
+    assert lib.pafu_select_topk(None, A, 10, -3, A, None, None, 0) == -2         # k < 0
+    assert lib.pafu_select_topk(None, A + 4, 10, 3, A, None, None, 0) == -4      # misaligned
+    assert lib.pafu_select_topk(None, A, 10, 3, None, None, None, 0) == -1       # NULL out
+
+
+def test_compact_rejects_bad_arguments():
+    lib = binding.library()
+    f = lib.pafu_compact_kv
+    ok = dict(K=A, V=A + 0x100000, SL=None, ld=1536, n=100, ids=A + 0x200000, count=50, N=12, D=128, dt=0,
+              Ko=A + 0x300000, Vo=A + 0x400000, SLo=None, ldo=1536)
+
+    def call(**kw):
+        a = dict(ok); a.update(kw)
+        return f(None, a["K"], a["V"], a["SL"], a["ld"], a["n"], a["ids"], a["count"], a["N"], a["D"], a["dt"],
+                 a["Ko"], a["Vo"], a["SLo"], a["ldo"])
+
+    assert call(K=None) == -1
+    assert call(ids=None) == -1
+    assert call(count=101) == -2
+    assert call(ld=1000) == -2                    # stride smaller than a row
+    assert call(dt=7) == -3
+    assert call(K=A + 8) == -4
+    assert call(ld=1540) == -4                    # 3080 B stride not a multiple of 16
+    assert call(Ko=A) == -6                       # in place is not allowed
+    assert call(SL=A + 0x500000) == -1            # SL without SL_out
+    assert call(count=0, K=None) == 0             # nothing to do
+
+
+def test_attention_rejects_bad_arguments():
+    lib = binding.library()
+    f = lib.pafu_chunk_attention
+    ok = dict(Q=A, Lq=64, Kc=A + 0x100000, Vc=A + 0x200000, nk=10, Kn=A + 0x300000, Vn=A + 0x400000, Lc=64, N=2,
+              D=64, ldq=128, ldc=128, ldn=128, ldo=128, LB=64, sc=0.0, O=A + 0x500000, od=0)
+
+    def call(**kw):
+        a = dict(ok); a.update(kw)
+        return f(None, a["Q"], a["Lq"], a["Kc"], a["Vc"], a["nk"], a["Kn"], a["Vn"], a["Lc"], a["N"], a["D"], a["ldq"],
+                 a["ldc"], a["ldn"], a["ldo"], a["LB"], a["sc"], a["O"], a["od"], None, 0)
+
+    assert call(D=96) == -2
+    assert call(Lq=0) == -2
+    assert call(LB=0) == -2
+    assert call(Lq=65) == -2                      # more queries than chunk tokens
+    assert call(Q=None) == -1
+    assert call(Kc=None) == -1
+    assert call(od=5) == -3
+    assert call(ldq=132) == -4
+    assert call(O=A) == -6
+
+
+def test_score_rejects_bad_arguments():
+    lib = binding.library()
+    f = lib.pafu_score
+
+    def call(x0=A, x1=None, x2=None, ns=1, T=10, Fs=128, ld=128, dt=0, W1=A + 0x100000, b1=None, W2=A + 0x200000,
+             b2=None, M=32, no=1, act=0, out=A + 0x300000, ws=None, wsb=0):
+        return f(None, x0, x1, x2, ns, T, Fs, ld, dt, W1, b1, W2, b2, M, no, act, out, ws, wsb)
+
+    assert call(x0=None) == -1
+    assert call(ns=2) == -1                       # second segment missing
+    assert call(ns=4) == -2
+    assert call(M=0) == -2
+    assert call(act=9) == -2
+    assert call(dt=3) == -3
+    assert call(ld=100) == -2
+    assert call(ld=132) == -4
+    assert call(no=12) == -5                      # averaging several outputs needs the workspace
+    assert call(T=0, x0=None) == 0
+
+
+def test_step_rejects_bad_arguments():
+    lib = binding.library()
+    a = binding.pafu_step_args()
+    assert lib.pafu_step(None, None) == -1
+    a.mode = 5
+    assert lib.pafu_step(None, ctypes.byref(a)) == -2
+    assert lib.pafu_step_layers(None, None, 2) == -1
+    assert lib.pafu_step_layers(None, None, 0) == 0
