@@ -1,0 +1,230 @@
+#!/usr/bin/env python3
+"""Benchmark of the PaFu-KV chunk step on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input: score all cached and
+chunk tokens with the S-MLP, select the top-k cached tokens, compact K/V/SL, and attend from the chunk's
+queries over the retained cache plus the chunk (pafu_step, SINGLE mode).  The default workload is the
+Wan-1.3B-shaped single layer in bf16 (12 heads x 128, 32760 cached + 4680 chunk tokens, budget 16380).
+
+Prints ONE JSON line: ms per step (inputs resident in HBM), a per-stage breakdown measured with events
+on the launch stream, the roofline of the dominant kernel (attention, dense bf16 MFMA), and the fp64
+oracle timed on this machine's host cores on a bounded sample of the same workload.
+"""
+
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+# HBM bytes per attention launch from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE, scaled by a copy kernel);
+# filled from the summaries under profiles/ (None = not measured for that workload).
+MEASURED_ATTENTION_TRAFFIC_BYTES = {}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="C1", choices=["C1", "C4", "C2", "C0"])
+    ap.add_argument("--block-len", type=int, default=0, help="L_B (0 = chunk length, the paper's setting)")
+    ap.add_argument("--structure", default="uniform", choices=["uniform", "coherent"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sets", type=int, default=3, help="input buffer sets rotated between steps")
+    return ap.parse_args()
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build measures one GPU only (the path has no multi-GPU part); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    from paper_2601_21896_amd import binding as B
+    from paper_2601_21896_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    B.library()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    n_layers = wl.C2_LAYERS if a.workload == "C2" else 1
+    cfg = wl.C1 if a.workload == "C2" else wl.CONFIGS[a.workload]
+    N, D, n, Lc, k, H, M = cfg.N, cfg.D, cfg.n, cfg.Lc, cfg.k, cfg.H, cfg.M
+    L_B = a.block_len or Lc
+    n_kept = min(k, n)
+    bf = torch.bfloat16
+    x_dt = bf if cfg.dtype == "bf16" else torch.float32
+    q = "bf16" if cfg.dtype == "bf16" else None
+
+    def to_dev(arr, bf16=False):
+        t = torch.from_numpy(np.ascontiguousarray(arr)).to(dev)
+        return t.to(bf) if bf16 else t
+
+    # ---- inputs: one generated layer; further layers / buffer sets are token-rolled copies (same
+    # distribution, different addresses) so that no step re-reads what the previous one left in cache
+    t0 = time.time()
+    d = wl.make_layer_inputs(cfg, structure=a.structure)
+    base = dict(
+        X=to_dev(np.concatenate([d["X_cache"], d["X_chunk"]]), cfg.dtype == "bf16"),
+        K=to_dev(d["K_cache"], True), V=to_dev(d["V_cache"], True),
+        Q=to_dev(d["Q"], True), Kn=to_dev(d["K_chunk"], True), Vn=to_dev(d["V_chunk"], True),
+    )
+    W1 = to_dev(d["W1"], cfg.dtype == "bf16")
+    W2, b1, b2 = to_dev(d["W2"]), None, None
+    n_sets = max(1, a.sets) if n_layers == 1 else 1
+    sets = []
+    for s in range(n_sets * n_layers):
+        if s == 0:
+            cur = base
+        else:
+            sh = 977 * s
+            cur = dict(X=torch.cat([torch.roll(base["X"][:n], sh, 0), torch.roll(base["X"][n:], sh, 0)]),
+                       K=torch.roll(base["K"], sh, 0), V=torch.roll(base["V"], sh, 0),
+                       Q=torch.roll(base["Q"], sh, 0), Kn=torch.roll(base["Kn"], sh, 0),
+                       Vn=torch.roll(base["Vn"], sh, 0))
+        cur.update(scores=torch.empty(n + Lc, device=dev), ids=torch.empty(max(n_kept, 1), dtype=torch.int32, device=dev),
+                   K_out=torch.empty(max(n_kept, 1), N, D, device=dev, dtype=bf),
+                   V_out=torch.empty(max(n_kept, 1), N, D, device=dev, dtype=bf),
+                   SL_out=torch.empty(max(n_kept, 1), device=dev), O=torch.empty(Lc, N, D, device=dev, dtype=bf))
+        cur["args"] = B.make_step_args(B.PAFU_MODE_SINGLE, N, D, n, Lc, k, L_B, cur["X"][:n], cur["X"][n:], W1, b1, W2,
+                                       b2, cur["K"], cur["V"], None, cur["Q"], cur["Kn"], cur["Vn"], cur["scores"],
+                                       cur["ids"], cur["K_out"], cur["V_out"], cur["SL_out"], cur["O"])
+        sets.append(cur)
+    torch.cuda.synchronize()
+    gen_s = time.time() - t0
+
+    def run_step(i):
+        if n_layers == 1:
+            B.pafu_step(sets[i % n_sets]["args"])
+        else:
+            B.pafu_step_layers([s["args"] for s in sets])
+
+    # ---- whole-step timing
+    for i in range(a.warmup):
+        run_step(i)
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for i in range(a.steps):
+        run_step(i)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t_start) * 1e3 / a.steps
+    ms_per_step = ev0.elapsed_time(ev1) / a.steps
+
+    # ---- per-stage timing (same buffers, stage entry points, events on the launch stream)
+    stage_names = ("score", "select", "compact", "attention")
+    stage_ms = {s: [] for s in stage_names}
+    reps = max(a.steps, 10) if n_layers == 1 else 2
+
+    def stage_calls(cur):
+        return (
+            lambda: B.pafu_score(cur["X"], W1, b1, W2, b2, cur["scores"]),
+            lambda: B.pafu_select_topk(cur["scores"], k, cur["ids"], n=n),
+            lambda: B.pafu_compact_kv(cur["K"], cur["V"], cur["scores"], cur["ids"], n_kept, cur["K_out"], cur["V_out"],
+                                      cur["SL_out"]),
+            lambda: B.pafu_chunk_attention(cur["Q"], cur["K_out"], cur["V_out"], n_kept, cur["Kn"], cur["Vn"], L_B,
+                                           cur["O"]),
+        )
+
+    for i in range(reps + 2):
+        for cur in (sets if n_layers > 1 else [sets[i % n_sets]]):
+            evs = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
+            calls = stage_calls(cur)
+            evs[0].record()
+            for j, c in enumerate(calls):
+                c()
+                evs[j + 1].record()
+            torch.cuda.synchronize()
+            if i >= 2:
+                for j, s in enumerate(stage_names):
+                    stage_ms[s].append(evs[j].elapsed_time(evs[j + 1]))
+    avg = {s: float(np.mean(v)) for s, v in stage_ms.items()}
+    mn = {s: float(np.min(v)) for s, v in stage_ms.items()}
+
+    # ---- algorithmic work per launch (one layer)
+    T = n + Lc
+    eb = 2 if cfg.dtype == "bf16" else 4
+    visible_pairs = Lc * n_kept + sum(min(Lc, (i // L_B + 1) * L_B) for i in range(Lc))
+    attn_flops = 4.0 * visible_pairs * D * N
+    bytes_score = T * H * eb + M * H * eb + T * 4
+    bytes_select = n * 4 + n_kept * 4
+    bytes_compact = 2 * (2 * n_kept * N * D * 2) + 2 * n_kept * 4 + n_kept * 4
+    attn_tflops = attn_flops / (avg["attention"] * 1e-3) / 1e12
+    stages = {
+        "score": {"ms": avg["score"], "min_ms": mn["score"], "GB/s": bytes_score / avg["score"] / 1e6,
+                  "frac_hbm": bytes_score / avg["score"] / 1e6 / PEAK_HBM_GBS,
+                  "TFLOP/s": 2.0 * T * H * M / avg["score"] / 1e9},
+        "select": {"ms": avg["select"], "min_ms": mn["select"], "GB/s": bytes_select / avg["select"] / 1e6},
+        "compact": {"ms": avg["compact"], "min_ms": mn["compact"], "GB/s": bytes_compact / avg["compact"] / 1e6,
+                    "frac_hbm": bytes_compact / avg["compact"] / 1e6 / PEAK_HBM_GBS},
+        "attention": {"ms": avg["attention"], "min_ms": mn["attention"], "TFLOP/s": attn_tflops,
+                      "frac_mfma": attn_tflops / PEAK_BF16_TFLOPS},
+    }
+    roofline = {"kernel": "chunk_attention_kernel", "bound": "mfma", "achieved": attn_tflops, "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": attn_tflops / PEAK_BF16_TFLOPS,
+                "traffic": MEASURED_ATTENTION_TRAFFIC_BYTES.get((a.workload, L_B == Lc)),
+                "flops_per_launch": attn_flops, "avg_launch_ms": avg["attention"]}
+
+    # ---- CPU baseline: the oracle as it stands, bounded sample of the same workload
+    cpu = None
+    if not a.no_cpu_baseline and a.workload in ("C1", "C0", "C2"):
+        from oracle import pafu_oracle as orc
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = len(os.sched_getaffinity(0))
+        rows = np.arange(0, Lc, max(1, Lc // 96))[:96] if Lc > 96 else np.arange(Lc)
+        c0 = time.perf_counter()
+        s_ref = orc.smlp_score(np.concatenate([d["X_cache"], d["X_chunk"]]), d["W1"], None, d["W2"], None)
+        c1 = time.perf_counter()
+        ids_ref = orc.select_topk(s_ref[:n].astype(np.float32), k)
+        c2 = time.perf_counter()
+        Kk, Vk, _ = orc.compact_kv(d["K_cache"], d["V_cache"], s_ref[:n].astype(np.float32), ids_ref)
+        c3 = time.perf_counter()
+        orc.chunk_attention(d["Q"], Kk, Vk, d["K_chunk"], d["V_chunk"], block_len=L_B, rows=rows)
+        c4 = time.perf_counter()
+        attn_full_ms = (c4 - c3) * 1e3 * (Lc / len(rows))
+        total = (c1 - c0) * 1e3 + (c2 - c1) * 1e3 + (c3 - c2) * 1e3 + attn_full_ms
+        cpu = {"value": total * n_layers, "unit": "ms per step (attention extrapolated from the sampled rows)",
+               "cores": int(cores), "kind": "oracle",
+               "sample": "full score/select/compact of one layer; attention on %d of %d query rows x all heads, "
+                         "scaled by %d/%d%s" % (len(rows), Lc, Lc, len(rows), "; x30 layers" if n_layers > 1 else ""),
+               "stages_ms": {"score": (c1 - c0) * 1e3, "select": (c2 - c1) * 1e3, "compact": (c3 - c2) * 1e3,
+                             "attention_extrapolated": attn_full_ms}}
+
+    out = {
+        "metric": "ms per AR chunk step (score+select+compact+attn)",
+        "value": ms_per_step, "unit": "ms", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": "%s: %d layer(s), %d heads x %d, cache %d tokens, chunk %d queries, budget %d, "
+                               "S-MLP %d->%d->%d, L_B=%d, salient=%s" % (a.workload, n_layers, N, D, n, Lc, k, H, M,
+                                                                          cfg.n_out, L_B, a.structure),
+                   "layers": n_layers, "input_sets": n_sets},
+        "wall_ms_per_step": wall_ms, "stages": stages, "roofline": roofline, "cpu_baseline": cpu,
+        "input_gen_s": gen_s,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

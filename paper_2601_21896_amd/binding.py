@@ -229,6 +229,9 @@ def make_step_args(mode, N, D, n, Lc, k, block_len, x_cache, x_chunk, W1, b1, W2
     a.K_out, a.V_out, a.SL_out, a.O = _ptr(K_out), _ptr(V_out), _ptr(SL_out), _ptr(O)
     a.workspace = _ptr(workspace)
     a.workspace_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    # the struct holds raw device pointers; keep the tensors alive for as long as the struct lives
+    a._keep = (xs_cache, xs_chunk, W1, b1, W2, b2, K_cache, V_cache, SL_in, Q, K_chunk, V_chunk, scores, ids, K_out,
+               V_out, SL_out, O, workspace)
     return a
 
 

@@ -1,0 +1,169 @@
+"""GPU parity of pafu_step / pafu_step_layers (SINGLE and ROLLOUT) against the oracle.
+
+Teacher-forced comparison: the device's own fp32 scores are fed to the oracle's selection, so ids and
+the compacted cache must match bit for bit; the scores themselves within 1e-3; attention within
+max-abs 2e-2 and relative Frobenius 5e-3."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import pafu_oracle as orc
+from paper_2601_21896_amd import binding as B
+from paper_2601_21896_amd import workloads as wl
+from tests.gpu_util import ATTN_MAX_ABS, ATTN_REL_FRO, DEV, SCORE_MAX_ABS, attn_errors, dev, host
+
+pytestmark = pytest.mark.gpu
+
+
+def _single(cfg, d, k, L_B, contiguous_features=True):
+    n, Lc, N, D = d["n"], cfg.Lc, cfg.N, cfg.D
+    dt = cfg.dtype
+    rb = wl.round_to_bf16
+    kv = {x: rb(d[x]) for x in ("K_cache", "V_cache", "Q", "K_chunk", "V_chunk")}
+    if contiguous_features:
+        X = dev(np.concatenate([d["X_cache"], d["X_chunk"]]), dt)
+        x_cache, x_chunk = X[:n], X[n:]
+    else:
+        x_cache, x_chunk = dev(d["X_cache"], dt), dev(d["X_chunk"], dt)
+    n_kept = min(k, n)
+    scores = torch.empty(n + Lc, device=DEV)
+    ids = torch.full((max(n_kept, 1),), -1, dtype=torch.int32, device=DEV)
+    K_out = torch.zeros(max(n_kept, 1), N, D, device=DEV, dtype=torch.bfloat16)
+    V_out = torch.zeros_like(K_out)
+    SL_out = torch.zeros(max(n_kept, 1), device=DEV)
+    O = torch.empty(Lc, N, D, device=DEV, dtype=torch.bfloat16)
+    # the argument struct holds raw pointers only: keep every device tensor alive next to it
+    w = [dev(d["W1"], dt), dev(d["b1"]), dev(d["W2"]), dev(d["b2"])]
+    t = [dev(kv["K_cache"], "bf16") if n else None, dev(kv["V_cache"], "bf16") if n else None,
+         dev(kv["Q"], "bf16"), dev(kv["K_chunk"], "bf16"), dev(kv["V_chunk"], "bf16")]
+    args = B.make_step_args(B.PAFU_MODE_SINGLE, N, D, n, Lc, k, L_B, x_cache if n else None, x_chunk,
+                            w[0], w[1], w[2], w[3], t[0], t[1], None, t[2], t[3], t[4],
+                            scores, ids, K_out, V_out, SL_out, O)
+    args._keep = (w, t, x_cache, x_chunk)
+    return args, kv, scores, ids, K_out, V_out, SL_out, O, n_kept
+
+
+def _check_single(cfg, d, k, L_B, args_pack):
+    args, kv, scores, ids, K_out, V_out, SL_out, O, n_kept = args_pack
+    torch.cuda.synchronize()
+    got_s = host(scores)
+    ref = orc.step_single(d["X_cache"], d["X_chunk"], d["W1"], d["b1"], d["W2"], d["b2"], kv["K_cache"], kv["V_cache"],
+                          kv["Q"], kv["K_chunk"], kv["V_chunk"], k, L_B, forced_scores_f32=got_s)
+    assert np.abs(got_s - ref["scores"]).max() < SCORE_MAX_ABS
+    assert np.array_equal(host(ids)[:n_kept], ref["ids"])
+    assert np.array_equal(host(K_out)[:n_kept], ref["K_kept"]) and np.array_equal(host(V_out)[:n_kept], ref["V_kept"])
+    assert np.array_equal(host(SL_out)[:n_kept], ref["SL_kept"])
+    max_abs, rel = attn_errors(host(O), ref["O"])
+    assert max_abs < ATTN_MAX_ABS and rel < ATTN_REL_FRO, (max_abs, rel)
+    # free-running check: indices may differ from the oracle's own selection only near the threshold
+    own = orc.select_topk(ref["scores"][: d["n"]].astype(np.float32), k)
+    diff = set(own.tolist()) ^ set(ref["ids"].tolist())
+    if diff and n_kept:
+        kth = np.sort(ref["scores"][: d["n"]])[::-1][n_kept - 1]
+        assert all(abs(ref["scores"][i] - kth) < SCORE_MAX_ABS for i in diff)
+
+
+@pytest.mark.parametrize("contig", [True, False])
+def test_step_single_c0(contig):
+    cfg = wl.C0
+    d = wl.make_layer_inputs(cfg, bias=True)
+    pack = _single(cfg, d, cfg.k, cfg.Lc, contiguous_features=contig)
+    B.pafu_step(pack[0])
+    _check_single(cfg, d, cfg.k, cfg.Lc, pack)
+
+
+@pytest.mark.parametrize("k_mode,L_B", [("half", 0), ("all", 0), ("more", 0), ("zero", 0), ("half", 60)])
+def test_step_single_c1_shaped(k_mode, L_B):
+    cfg = wl.scaled(wl.C1, frame_tokens=60, cache_frames=9, chunk_frames=3, k=270)     # n = 540, Lc = 180
+    d = wl.make_layer_inputs(cfg)
+    k = {"half": 270, "all": 540, "more": 1000, "zero": 0}[k_mode]
+    L_B = L_B or cfg.Lc
+    pack = _single(cfg, d, k, L_B)
+    B.pafu_step(pack[0])
+    _check_single(cfg, d, k, L_B, pack)
+    if k_mode in ("all", "more"):      # budget >= cache: cache unchanged
+        assert np.array_equal(host(pack[4]), wl.round_to_bf16(d["K_cache"]))
+
+
+def test_step_single_empty_cache():
+    cfg = wl.scaled(wl.C1, frame_tokens=50, cache_frames=0, chunk_frames=2, k=10)
+    d = wl.make_layer_inputs(cfg)
+    pack = _single(cfg, d, 10, cfg.Lc)
+    B.pafu_step(pack[0])
+    _check_single(cfg, d, 10, cfg.Lc, pack)
+
+
+def test_step_layers_independent():
+    cfg = wl.scaled(wl.C1, frame_tokens=40, cache_frames=6, chunk_frames=2, k=120)
+    layers = [wl.make_layer_inputs(cfg, seed=wl.BASE_SEED + 2 + 1000 * l) for l in range(3)]
+    packs = [_single(cfg, d, cfg.k, cfg.Lc) for d in layers]
+    B.pafu_step_layers([p[0] for p in packs])
+    ids_seen = []
+    for d, p in zip(layers, packs):
+        _check_single(cfg, d, cfg.k, cfg.Lc, p)
+        ids_seen.append(host(p[3]).tolist())
+    assert ids_seen[0] != ids_seen[1]
+
+
+def _rollout(cfg, k, n_chunks, L_B, stop_at=None, resume=None):
+    """Runs the device rollout beside the oracle's (teacher-forced on the chunk scores)."""
+    N, D, Lc = cfg.N, cfg.D, cfg.Lc
+    W1, b1, W2, b2 = wl.make_rollout_weights(cfg, bias=True)
+    dW1, db1, dW2, db2 = dev(W1, "bf16"), dev(b1), dev(W2), dev(b2)
+    cap = k + Lc
+    slabs = [dict(K=torch.zeros(cap, N, D, device=DEV, dtype=torch.bfloat16),
+                  V=torch.zeros(cap, N, D, device=DEV, dtype=torch.bfloat16),
+                  SL=torch.zeros(cap, device=DEV)) for _ in range(2)]
+    st = orc.RolloutState(N, D, np.float32)
+    n, cur, t0 = 0, 0, 0
+    if resume is not None:
+        n, t0 = resume["n"], resume["t"]
+        for key in ("K", "V", "SL"):
+            slabs[0][key][:n] = resume[key]
+        st = resume["oracle"].copy()
+    ids = torch.empty(max(k, 1), dtype=torch.int32, device=DEV)
+    O = torch.empty(Lc, N, D, device=DEV, dtype=torch.bfloat16)
+    sizes = []
+    for t in range(t0, n_chunks):
+        c = wl.make_chunk_inputs(cfg, t)
+        src, dst = slabs[cur], slabs[1 - cur]
+        n_kept = min(k, n)
+        args = B.make_step_args(B.PAFU_MODE_ROLLOUT, N, D, n, Lc, k, L_B, None, dev(c["X_chunk"], "bf16"), dW1, db1,
+                                dW2, db2, src["K"], src["V"], src["SL"], dev(c["Q"], "bf16"), dev(c["K_chunk"], "bf16"),
+                                dev(c["V_chunk"], "bf16"), None, ids, dst["K"], dst["V"], dst["SL"], O)
+        B.pafu_step(args)
+        torch.cuda.synchronize()
+        s_chunk = host(dst["SL"][n_kept:n_kept + Lc])
+        out = orc.rollout_step(st, c["X_chunk"], W1, b1, W2, b2, c["Q"], c["K_chunk"], c["V_chunk"], k, L_B,
+                               forced_chunk_scores_f32=s_chunk)
+        assert np.abs(s_chunk - out["s_chunk"]).max() < SCORE_MAX_ABS
+        assert np.array_equal(host(ids)[:n_kept], out["ids"]), t
+        n = n_kept + Lc
+        assert n == st.n
+        assert np.array_equal(host(dst["K"][:n]), st.K) and np.array_equal(host(dst["V"][:n]), st.V), t
+        assert np.array_equal(host(dst["SL"][:n]), st.SL), t
+        max_abs, rel = attn_errors(host(O), out["O"])
+        assert max_abs < ATTN_MAX_ABS and rel < ATTN_REL_FRO, (t, max_abs, rel)
+        sizes.append(n)
+        cur = 1 - cur
+        if stop_at is not None and t + 1 == stop_at:
+            return dict(n=n, t=t + 1, K=slabs[cur]["K"][:n].clone(), V=slabs[cur]["V"][:n].clone(),
+                        SL=slabs[cur]["SL"][:n].clone(), oracle=st.copy()), sizes
+    return dict(n=n, K=slabs[cur]["K"][:n].clone(), V=slabs[cur]["V"][:n].clone(), SL=slabs[cur]["SL"][:n].clone()), sizes
+
+
+def test_rollout_matches_oracle_and_resumes_bit_identically():
+    cfg = wl.scaled(wl.C1, frame_tokens=30, chunk_frames=3, cache_frames=0, k=240)     # Lc = 90, k = 8 frames
+    full, sizes = _rollout(cfg, 240, 8, cfg.Lc)
+    assert sizes == [90, 180, 270, 330, 330, 330, 330, 330]
+    snap, _ = _rollout(cfg, 240, 8, cfg.Lc, stop_at=4)
+    resumed, _ = _rollout(cfg, 240, 8, cfg.Lc, resume=snap)
+    for key in ("K", "V", "SL"):
+        assert torch.equal(full[key], resumed[key])
+
+
+def test_rollout_full_budget_never_evicts():
+    cfg = wl.scaled(wl.C1, frame_tokens=20, chunk_frames=2, cache_frames=0, k=10 ** 6)
+    N, D, Lc = cfg.N, cfg.D, cfg.Lc
+    out, sizes = _rollout(wl.scaled(cfg, k=400), 400, 5, 20)
+    assert sizes == [40, 80, 120, 160, 200]
