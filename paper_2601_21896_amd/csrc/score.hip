@@ -95,10 +95,8 @@ constexpr int kScThreads = 256;
 constexpr int kScTokPerWave = 32;
 constexpr int kScTokPerWg = 128;
 constexpr int kScSlab = 64;                 // features per LDS slab
-constexpr int kScMBlocks = 8;               // 32-row hidden blocks per pass (256 hidden units)
 constexpr int kScRowBytes = kScSlab * 2 + 16;  // 144 B: padded so that 16 consecutive rows hit distinct banks
-constexpr int kScBufBytes = kScMBlocks * 32 * kScRowBytes;
-constexpr int kScLdsBytes = 2 * kScBufBytes;
+constexpr int sc_lds_bytes(int mb) { return 2 * mb * 32 * kScRowBytes; }
 
 __device__ __forceinline__ float fast_silu(float h) {
   // h * sigmoid(h), sigmoid via exp2 and a reciprocal
@@ -106,6 +104,8 @@ __device__ __forceinline__ float fast_silu(float h) {
   return h * __builtin_amdgcn_rcpf(1.0f + e);
 }
 
+// MB = 32-row hidden blocks per pass over X (MB*32 hidden units are accumulated at once).
+template <int MB>
 __global__ __launch_bounds__(kScThreads, 2) void score_mfma_kernel(const unsigned short* __restrict__ x0,
                                                                    const unsigned short* __restrict__ x1,
                                                                    const unsigned short* __restrict__ x2, int T,
@@ -126,9 +126,10 @@ __global__ __launch_bounds__(kScThreads, 2) void score_mfma_kernel(const unsigne
   const int w_row = tid >> 3, w_chunk = tid & 7;
 
   float partial = 0.f;
+  constexpr int kScMBlocks = MB;
+  constexpr int kScBufBytes = MB * 32 * kScRowBytes;
 #pragma unroll 1
   for (int mp = 0; mp < M; mp += kScMBlocks * 32) {
-    const int nblk = (M - mp) / 32 < kScMBlocks ? (M - mp) / 32 : kScMBlocks;
     f32x16 acc[kScMBlocks];
 #pragma unroll
     for (int b = 0; b < kScMBlocks; ++b)
@@ -137,54 +138,53 @@ __global__ __launch_bounds__(kScThreads, 2) void score_mfma_kernel(const unsigne
 
     u32x4 wreg[kScMBlocks];
     bf16x8 xreg[4];
-    auto load_slab = [&](int s) {
-      const unsigned short* wsrc = W1 + (long long)(mp + w_row) * F + (long long)s * kScSlab + w_chunk * 8;
-#pragma unroll
-      for (int i = 0; i < kScMBlocks; ++i)
-        if (i < nblk) wreg[i] = *reinterpret_cast<const u32x4*>(wsrc + (long long)i * 32 * F);
-      const int seg = s / slabs_per_seg;
-      const int fo = (s - seg * slabs_per_seg) * kScSlab;
-      const unsigned short* xs = seg == 0 ? x0 : (seg == 1 ? x1 : x2);
-      const unsigned short* xsrc = xs + (long long)tokc * ld_x + fo + 8 * g;
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) xreg[kk] = *reinterpret_cast<const bf16x8*>(xsrc + kk * 16);
-    };
-    auto store_slab = [&](int buf) {
-      unsigned char* dst = lds + buf * kScBufBytes + w_row * kScRowBytes + w_chunk * 16;
-#pragma unroll
-      for (int i = 0; i < kScMBlocks; ++i)
-        if (i < nblk) *reinterpret_cast<u32x4*>(dst + i * 32 * kScRowBytes) = wreg[i];
-    };
+    const unsigned short* wbase = W1 + (long long)(mp + w_row) * F + w_chunk * 8;
+#define PAFU_LOAD_SLAB(S)                                                                          \
+  do {                                                                                             \
+    const unsigned short* wsrc = wbase + (long long)(S) * kScSlab;                                 \
+    _Pragma("unroll") for (int i = 0; i < kScMBlocks; ++i)                                         \
+        wreg[i] = *reinterpret_cast<const u32x4*>(wsrc + (long long)i * 32 * F);                   \
+    const int seg = (S) / slabs_per_seg;                                                           \
+    const int fo = ((S) - seg * slabs_per_seg) * kScSlab;                                          \
+    const unsigned short* xs = seg == 0 ? x0 : (seg == 1 ? x1 : x2);                               \
+    const unsigned short* xsrc = xs + (long long)tokc * ld_x + fo + 8 * g;                         \
+    _Pragma("unroll") for (int kk = 0; kk < 4; ++kk)                                               \
+        xreg[kk] = *reinterpret_cast<const bf16x8*>(xsrc + kk * 16);                               \
+  } while (0)
+#define PAFU_STORE_SLAB(BUF)                                                                       \
+  do {                                                                                             \
+    unsigned char* dst = lds + (BUF) * kScBufBytes + w_row * kScRowBytes + w_chunk * 16;           \
+    _Pragma("unroll") for (int i = 0; i < kScMBlocks; ++i)                                         \
+        *reinterpret_cast<u32x4*>(dst + i * 32 * kScRowBytes) = wreg[i];                           \
+  } while (0)
 
-    load_slab(0);
+    PAFU_LOAD_SLAB(0);
     __syncthreads();  // every wave is done with the LDS contents of the previous pass
-    store_slab(0);
+    PAFU_STORE_SLAB(0);
     __syncthreads();
 #pragma unroll 1
     for (int s = 0; s < n_slabs; ++s) {
       bf16x8 xcur[4];
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) xcur[kk] = xreg[kk];
-      if (s + 1 < n_slabs) load_slab(s + 1);
+      if (s + 1 < n_slabs) PAFU_LOAD_SLAB(s + 1);
       const unsigned char* buf = lds + (s & 1) * kScBufBytes + c * kScRowBytes + g * 16;
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
 #pragma unroll
         for (int b = 0; b < kScMBlocks; ++b) {
-          if (b < nblk) {
-            const bf16x8 a = *reinterpret_cast<const bf16x8*>(buf + b * 32 * kScRowBytes + kk * 32);
-            acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, xcur[kk], acc[b], 0, 0, 0);
-          }
+          const bf16x8 a = *reinterpret_cast<const bf16x8*>(buf + b * 32 * kScRowBytes + kk * 32);
+          acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, xcur[kk], acc[b], 0, 0, 0);
         }
       }
-      if (s + 1 < n_slabs) store_slab((s + 1) & 1);
+      if (s + 1 < n_slabs) PAFU_STORE_SLAB((s + 1) & 1);
       __syncthreads();
     }
     // activation and second layer for this pass's hidden units; lane holds token c, units
     // mp + 32 b + 8 (r/4) + 4 g + (r%4)
 #pragma unroll
     for (int b = 0; b < kScMBlocks; ++b) {
-      if (b < nblk) {
+      {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const int m0 = mp + 32 * b + 8 * q + 4 * g;
@@ -208,6 +208,8 @@ __global__ __launch_bounds__(kScThreads, 2) void score_mfma_kernel(const unsigne
       }
     }
   }
+#undef PAFU_LOAD_SLAB
+#undef PAFU_STORE_SLAB
   partial += __shfl_xor(partial, 32);
   if (g == 0 && tok < T) out[tok] = partial + (b2bar ? *b2bar : 0.f);
 }
@@ -231,18 +233,27 @@ int launch_score(hipStream_t st, const void* x0, const void* x1, const void* x2,
   const int F = n_seg * Fs;
   const bool mfma = x_dtype == PAFU_BF16 && Fs % kScSlab == 0 && M % 32 == 0 && ld_x % 8 == 0;
   if (mfma) {
-    static bool attr_set = false;
-    if (!attr_set) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(score_mfma_kernel),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, kScLdsBytes);
-      if (e != hipSuccess) return record_hip_error(e);
-      attr_set = true;
-    }
     const int grid = (T + kScTokPerWg - 1) / kScTokPerWg;
-    hipLaunchKernelGGL(score_mfma_kernel, dim3(grid), dim3(kScThreads), kScLdsBytes, st,
-                       static_cast<const unsigned short*>(x0), static_cast<const unsigned short*>(x1),
-                       static_cast<const unsigned short*>(x2), T, Fs, F, ld_x, static_cast<const unsigned short*>(W1),
-                       b1, w2bar, b2bar, M, act, out);
+    const int blocks = M / 32;
+#define PAFU_SCORE_CASE(MB)                                                                                          \
+  do {                                                                                                               \
+    static bool attr_set = false;                                                                                    \
+    if (!attr_set) {                                                                                                 \
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(score_mfma_kernel<MB>),                       \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, sc_lds_bytes(MB));              \
+      if (e != hipSuccess) return record_hip_error(e);                                                               \
+      attr_set = true;                                                                                               \
+    }                                                                                                                \
+    hipLaunchKernelGGL(score_mfma_kernel<MB>, dim3(grid), dim3(kScThreads), sc_lds_bytes(MB), st,                    \
+                       static_cast<const unsigned short*>(x0), static_cast<const unsigned short*>(x1),               \
+                       static_cast<const unsigned short*>(x2), T, Fs, F, ld_x, static_cast<const unsigned short*>(W1), \
+                       b1, w2bar, b2bar, M, act, out);                                                               \
+  } while (0)
+    if (blocks % 8 == 0) PAFU_SCORE_CASE(8);
+    else if (blocks % 4 == 0) PAFU_SCORE_CASE(4);
+    else if (blocks % 2 == 0) PAFU_SCORE_CASE(2);
+    else PAFU_SCORE_CASE(1);
+#undef PAFU_SCORE_CASE
   } else {
     const int grid = (T + 15) / 16;
     if (x_dtype == PAFU_BF16)
