@@ -192,7 +192,9 @@ def main():
             cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
         except Exception:
             cores = len(os.sched_getaffinity(0))
-        rows = np.arange(0, Lc, max(1, Lc // 96))[:96] if Lc > 96 else np.arange(Lc)
+        # about 10-30 s of CPU work: every query row at the Wan-1.3B layer, a strided sample above that
+        n_rows = Lc if Lc * (n_kept + Lc) * N <= 1.3e9 else max(96, int(1.3e9 / ((n_kept + Lc) * N)))
+        rows = np.arange(Lc) if n_rows >= Lc else np.unique(np.linspace(0, Lc - 1, n_rows).astype(np.int64))
         c0 = time.perf_counter()
         s_ref = orc.smlp_score(np.concatenate([d["X_cache"], d["X_chunk"]]), d["W1"], None, d["W2"], None)
         c1 = time.perf_counter()
