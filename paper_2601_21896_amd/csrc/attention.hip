@@ -26,19 +26,6 @@
 // by row, so no concatenated copy exists.
 #include "pafu_internal.h"
 
-#ifndef PAFU_ATTN_EXPERIMENT
-#define PAFU_ATTN_EXPERIMENT 0  // timing experiments only: 1 no softmax, 2 no MFMA, 3 no tile loads
-#endif
-#ifndef PAFU_ATTN_PRIO
-#define PAFU_ATTN_PRIO 1  // 0 none, 1 matrix phase high, 2 vector phase high
-#endif
-#ifndef PAFU_ATTN_NOP
-#define PAFU_ATTN_NOP -1  // s_nop after every MFMA of the matrix phase (-1 none)
-#endif
-#ifndef PAFU_ATTN_MID_BARRIER
-#define PAFU_ATTN_MID_BARRIER 1
-#endif
-
 namespace pafu {
 namespace {
 
@@ -98,7 +85,6 @@ __device__ __forceinline__ void wait_vmcnt() {
 
 template <int D, bool OUT_F32>
 __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnParams p) {
-  constexpr bool kMidBarrier = PAFU_ATTN_MID_BARRIER;
   constexpr int ROWB = 2 * D;            // bytes per K/V row of one head
   constexpr int TILEB = kAtBK * ROWB;    // bytes per K (or V) tile
   constexpr int CH = D / 8;              // 16-byte chunks per row
@@ -159,7 +145,7 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnPara
       const bool in_cache = kidx < p.n_kept;
       const char* src = (in_cache ? base_c : base_n) + (unsigned long long)(unsigned)kidx * (unsigned long long)(in_cache ? ldc_b : ldn_b) + chunk_of[j] * 16;
       lds_byte* dst = ring + stage * TILEB + (wave + kAtWaves * j) * 1024;
-      if (PAFU_ATTN_EXPERIMENT != 3) dma_row_chunks(src, __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)dst));
+      dma_row_chunks(src, __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)dst));
     }
   };
   // K of tile kt and V of tile kt - 1 travel together (V is consumed one iteration after K)
@@ -203,7 +189,7 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnPara
 
   // matrix phase of iteration t: S^T(t) = K(t) Q^T  and  O^T += V(t-1)^T P(t-1)^T
   auto matrix_phase = [&](int t) {
-    if (PAFU_ATTN_PRIO == 1) __builtin_amdgcn_s_setprio(1);
+    __builtin_amdgcn_s_setprio(1);
     if (t < n_tiles) {
       const lds_byte* kt = k_ring + (t % kAtStages) * TILEB + k_off;
 #pragma unroll
@@ -216,9 +202,7 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnPara
         for (int kb = 0; kb < 2; ++kb) {  // the two key blocks alternate: no back-to-back dependent MFMAs
           const bf16x8 a =
               *(const __attribute__((address_space(3))) bf16x8*)(kt + kb * 32 * ROWB + (((2 * kk) ^ kx2) << 4));
-          if (PAFU_ATTN_EXPERIMENT == 2) s[kb][kk] += (float)a[0];
-          else s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], s[kb], 0, 0, 0);
-          if (PAFU_ATTN_NOP >= 0) asm volatile("s_nop %0" ::"n"(PAFU_ATTN_NOP >= 0 ? PAFU_ATTN_NOP : 0));
+          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], s[kb], 0, 0, 0);
         }
       }
     }
@@ -233,20 +217,16 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnPara
           const s16x4 hi =
               __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(a0 + 8 * ROWB));
           const s16x8 a16 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          if (PAFU_ATTN_EXPERIMENT == 2) o[b][ks] += (float)a16[0];
-          else o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a16), pf[ks], o[b], 0, 0, 0);
-          if (PAFU_ATTN_NOP >= 0) asm volatile("s_nop %0" ::"n"(PAFU_ATTN_NOP >= 0 ? PAFU_ATTN_NOP : 0));
+          o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a16), pf[ks], o[b], 0, 0, 0);
         }
       }
     }
-    if (PAFU_ATTN_PRIO == 1) __builtin_amdgcn_s_setprio(0);
+    __builtin_amdgcn_s_setprio(0);
   };
 
   // vector phase of iteration t: online softmax of S^T(t) -> P^T(t), rescale of O^T
   auto vector_phase = [&](int t) {
     if (t >= n_tiles) return;
-    if (PAFU_ATTN_EXPERIMENT == 1) return;
-    if (PAFU_ATTN_PRIO == 2) __builtin_amdgcn_s_setprio(1);
     // block mask / ragged tail: key index of register r is t*64 + 32 kb + 8 (r/4) + 4 g + (r%4)
     if ((t + 1) * kAtBK > lim_min) {
 #pragma unroll
@@ -285,7 +265,6 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnPara
       m_run = m_new;
     }
     l_run += psum;
-    if (PAFU_ATTN_PRIO == 2) __builtin_amdgcn_s_setprio(0);
   };
 
   // ---- prologue: fill the ring (K tiles 0..S-2, V tiles 0..S-3), then run the phases.
@@ -304,7 +283,7 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnPara
     for (int t = 0; t < n_iter; ++t) {
       issue_tile(t + kAtStages - 1);
       matrix_phase(t);
-      if (kMidBarrier) __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_s_barrier();
       vector_phase(t);
       wait_vmcnt<2 * LPT*(kAtStages - 2)>();
       __builtin_amdgcn_s_barrier();
@@ -314,7 +293,7 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnPara
     for (int t = 0; t < n_iter; ++t) {
       issue_tile(t + kAtStages - 1);
       if (t > 0) vector_phase(t - 1);
-      if (kMidBarrier) __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_s_barrier();
       matrix_phase(t);
       wait_vmcnt<2 * LPT*(kAtStages - 2)>();
       __builtin_amdgcn_s_barrier();
