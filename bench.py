@@ -28,7 +28,10 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
 # HBM bytes per attention launch from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE, scaled by a copy kernel);
 # filled from the summaries under profiles/ (None = not measured for that workload).
-MEASURED_ATTENTION_TRAFFIC_BYTES = {}
+MEASURED_ATTENTION_TRAFFIC_BYTES = {
+    # profiles/step_C1_hbm_traffic_pmc.md: 512543.1 KiB x 1.98 fetched + 14040.8 KiB written
+    ("C1", True): int((512543.1 * 1.98 + 14040.8) * 1024),
+}
 
 
 def parse():
@@ -36,12 +39,74 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="C1", choices=["C1", "C4", "C2", "C0"])
+    ap.add_argument("--workload", default="C1", choices=["C1", "C4", "C2", "C0", "C3"])
+    ap.add_argument("--budget", type=int, default=0, help="C3 only: cache budget k in tokens (default 8 frames = 12480)")
     ap.add_argument("--block-len", type=int, default=0, help="L_B (0 = chunk length, the paper's setting)")
     ap.add_argument("--structure", default="uniform", choices=["uniform", "coherent"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sets", type=int, default=3, help="input buffer sets rotated between steps")
     return ap.parse_args()
+
+
+def rollout(a, torch, np, B, wl):
+    """C3: 60 sequential chunks at the Wan-1.3B layer shapes, fixed budget; steady-state ms per step."""
+    dev = "cuda:0"
+    bf = torch.bfloat16
+    cfg = wl.C1
+    N, D, Lc, H, M = cfg.N, cfg.D, cfg.Lc, cfg.H, cfg.M
+    k = a.budget or wl.C3_K
+    n_chunks = wl.C3_CHUNKS
+    cap = k + Lc
+    W1n, b1n, W2n, b2n = wl.make_rollout_weights(cfg)
+    t = lambda arr, b16=False: (torch.from_numpy(np.ascontiguousarray(arr)).to(dev).to(bf) if b16
+                                else torch.from_numpy(np.ascontiguousarray(arr)).to(dev))
+    W1, W2 = t(W1n, True), t(W2n)
+    pool = []
+    for c in range(4):      # chunk inputs cycle through 4 generated sets (fresh K/V/features per chunk seed)
+        ci = wl.make_chunk_inputs(cfg, c)
+        pool.append(dict(X=t(ci["X_chunk"], True), Q=t(ci["Q"], True), K=t(ci["K_chunk"], True), V=t(ci["V_chunk"], True)))
+    slabs = [dict(K=torch.zeros(cap, N, D, device=dev, dtype=bf), V=torch.zeros(cap, N, D, device=dev, dtype=bf),
+                  SL=torch.zeros(cap, device=dev)) for _ in range(2)]
+    ids = torch.empty(max(k, 1), dtype=torch.int32, device=dev)
+    O = torch.empty(Lc, N, D, device=dev, dtype=bf)
+    times, sizes = [], []
+    for rep in range(2):    # first pass warms up, second is timed
+        n, cur = 0, 0
+        times, sizes = [], []
+        for step in range(n_chunks):
+            c = pool[step % len(pool)]
+            src, dst = slabs[cur], slabs[1 - cur]
+            args = B.make_step_args(B.PAFU_MODE_ROLLOUT, N, D, n, Lc, k, Lc, None, c["X"], W1, None, W2, None, src["K"],
+                                    src["V"], src["SL"], c["Q"], c["K"], c["V"], None, ids, dst["K"], dst["V"],
+                                    dst["SL"], O)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            B.pafu_step(args)
+            e1.record()
+            torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1))
+            n = min(k, n) + Lc
+            sizes.append(n)
+            cur = 1 - cur
+    steady = times[5:]
+    n_steady = sizes[-1]
+    n_kept = min(k, n_steady)
+    flops = 4.0 * Lc * (n_kept + Lc) * D * N
+    peak_cache = 2 * (cap * N * D * 2 * 2 + cap * 4)
+    out = {
+        "metric": "ms per AR chunk step (score+select+compact+attn)", "value": float(np.median(steady)), "unit": "ms",
+        "n_gpus": 1, "steps": len(steady), "warmup": n_chunks + 5, "ms_per_step": float(np.median(steady)),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "C3: %d-chunk rollout, 12 heads x 128, chunk %d queries, budget %d tokens, steady cache "
+                               "%d tokens, S-MLP %d->%d->1" % (n_chunks, Lc, k, n_steady, H, M)},
+        "min_ms": float(np.min(steady)), "first_steps_ms": [float(x) for x in times[:5]], "cache_sizes_first_steps": sizes[:6],
+        "peak_cache_bytes": peak_cache,
+        "roofline": {"kernel": "chunk_attention_kernel", "bound": "mfma", "achieved": None, "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": None, "traffic": None, "flops_per_launch": flops,
+                     "note": "whole-step time only; per-kernel times come from the rocprofv3 summary"},
+        "cpu_baseline": None,
+    }
+    print(json.dumps(out))
 
 
 def main():
@@ -63,6 +128,9 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
 
+    if a.workload == "C3":
+        rollout(a, torch, np, B, wl)
+        return
     n_layers = wl.C2_LAYERS if a.workload == "C2" else 1
     cfg = wl.C1 if a.workload == "C2" else wl.CONFIGS[a.workload]
     N, D, n, Lc, k, H, M = cfg.N, cfg.D, cfg.n, cfg.Lc, cfg.k, cfg.H, cfg.M
