@@ -3,11 +3,11 @@
 // App. A: L_B = chunk length at inference (then the chunk attends to all of itself).
 //
 // Flash-style kernel for gfx950: bf16 MFMA (v_mfma_f32_32x32x16_bf16), fp32 online softmax, fp32
-// accumulation.  One workgroup = 8 waves = 256 queries of one head; each wave owns 32 queries and
-// walks the key axis in tiles of 64 keys.  Both products are computed TRANSPOSED:
+// accumulation.  One workgroup = 8 waves = 256 queries of one head; each wave owns 32 queries (one
+// column block) and walks the key axis in tiles of 64 keys.  Both products are TRANSPOSED:
 //
-//   S^T[key, q] = K_tile . Q^T         (A = K rows from LDS, B = Q^T held in registers for the whole loop)
-//   O^T[d,   q] = V_tile^T . P^T       (A = V^T via transposing LDS reads, B = P^T straight from the S^T
+//   S^T[key, q] = K_blk . Q^T          (A = K rows from LDS, B = Q^T held in registers for the whole loop)
+//   O^T[d,   q] = V_blk^T . P^T        (A = V^T via transposing LDS reads, B = P^T straight from the S^T
 //                                       accumulator registers)
 //
 // In the 32x32 accumulator layout a lane holds 16 rows of ONE column, so with queries as columns the
@@ -15,15 +15,19 @@
 // lane, and the accumulator registers of S^T already ARE the B operand of the second product (its
 // contraction index - the key - may be enumerated in any order as long as V^T uses the same order).
 //
-// Scheduling: the two waves that share a SIMD alternate roles every phase ("ping-pong"): while one
-// runs its matrix phase (S^T of the next tile and O^T update of the current one, 32 MFMAs), the other
-// runs its vector phase (online softmax of the S^T it just produced).  A workgroup barrier ends each
-// phase, which keeps the two groups exactly one phase apart, so the matrix and vector pipes of every
-// SIMD are both busy.  K/V tiles stream from global memory straight into a 4-deep LDS ring
-// (global_load_lds, no staging registers) several phases ahead of their use; rows are stored with an
-// XOR swizzle of their 16-byte chunks so that both the b128 K reads and the transposing V reads are
-// bank-conflict free without padding.  The two key segments (retained cache, chunk) are addressed row
-// by row, so no concatenated copy exists.
+// Scheduling.  On this chip the matrix and vector pipes only overlap reliably for instructions of the
+// SAME wave (a wave with a matrix instruction waiting at issue blocks the vector instructions of its
+// SIMD neighbour), so each wave is software-pipelined by hand: step t issues the 16 MFMAs of S^T(t+1)
+// and the 16 MFMAs that add tile t-1 to O^T, and after each of them a slice of the online softmax of
+// tile t (vector ALU).  Two such waves share a SIMD and fill each other's stalls.  The running maximum is only raised when it
+// grows by more than 2^8 (the result is mathematically unchanged), which makes the O^T rescale a rare,
+// out-of-line event.
+//
+// K/V tiles (64 keys) stream from global memory straight into a 4-deep LDS ring (global_load_lds, no
+// staging registers) three tiles ahead of their use; rows are stored with an XOR swizzle of their
+// 16-byte chunks so that both the b128 K reads and the transposing V reads are bank-conflict free
+// without padding.  The two key segments (retained cache, chunk) are addressed row by row, so no
+// concatenated copy exists.
 #include "pafu_internal.h"
 
 namespace pafu {
@@ -34,6 +38,17 @@ typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+
+// P^T fragments are kept as 4 dwords of packed bf16 pairs (the B operand of the second product)
+__device__ __forceinline__ bf16x8 as_bf16x8(const u32x4& v) { return __builtin_bit_cast(bf16x8, v); }
+__device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
+  bf16x2 t;
+  t[0] = (__bf16)lo;
+  t[1] = (__bf16)hi;
+  return __builtin_bit_cast(unsigned, t);
+}
 
 struct AttnParams {
   const unsigned short* Q;
@@ -50,13 +65,13 @@ struct AttnParams {
 constexpr int kAtWaves = 8;
 constexpr int kAtThreads = kAtWaves * 64;
 constexpr int kAtBQ = kAtWaves * 32;  // queries per workgroup
-constexpr int kAtBK = 64;             // keys per tile
+constexpr int kAtTileKeys = 64;       // keys per LDS tile = keys per pipeline step
 constexpr int kAtStages = 4;          // LDS ring depth (tiles)
+constexpr float kAtLazyLog2 = 8.0f;   // raise the running maximum only when it grows by more than 2^8
 
-constexpr int attn_lds_bytes(int D) { return 2 * kAtStages * kAtBK * 2 * D; }
+constexpr int attn_lds_bytes(int D) { return 2 * kAtStages * kAtTileKeys * 2 * D; }
 
 typedef __attribute__((address_space(3))) unsigned char lds_byte;
-typedef __attribute__((address_space(1))) const void global_cvoid;
 
 __device__ __forceinline__ float half_swap_max(float x) {
   const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
@@ -83,43 +98,168 @@ __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
+__device__ __forceinline__ bf16x8 lds_read_k(const lds_byte* p) {
+  return *(const __attribute__((address_space(3))) bf16x8*)p;
+}
+// V^T fragment: two transposing reads, 8 key rows apart
+__device__ __forceinline__ bf16x8 lds_read_vt(const lds_byte* p, int row_bytes8) {
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p);
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p + row_bytes8));
+  return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+// Pipeline step t for one wave (32 queries), one straight-line block:
+//   matrix pipe : S^T(t+1) = K(t+1) Q^T into s_nxt;  O^T += V(t-1)^T P(t-1)^T from p_prev
+//   vector pipe : online softmax of s_cur = S^T(t) -> p_cur = P^T(t), running max / sum,
+// with the vector work sliced between the MFMAs.  Edge cases are handled by the caller through the operands
+// (masked elements of s_cur set to -inf beforehand, p_prev = 0 before the first tile, a clamped K tile when
+// there is no next tile), so this is the only implementation of the step.
+// s_*[kb] = key block kb (32 keys) of the tile; p_*[ks] = 16-key slice ks of the tile.
+template <int D>
+__device__ __forceinline__ void attn_step(const f32x16 (&s_cur)[2], f32x16 (&s_nxt)[2], const u32x4 (&p_prev)[4],
+                                          u32x4 (&p_cur)[4], f32x16 (&o)[D / 32], const bf16x8 (&qf)[D / 16],
+                                          float& msc, float& l_run, const lds_byte* k_tile, const lds_byte* v_tile,
+                                          int kx2, int vx2, float sc) {
+  constexpr int ROWB = 2 * D;
+  constexpr int KD = D / 16;
+  constexpr int DB = D / 32;
+  constexpr int NS = 2 * KD;       // MFMAs of S^T(t+1): 2 key blocks x KD contraction steps
+  constexpr int NP = 4 * DB;       // MFMAs of the O^T update: 4 key slices x DB row blocks
+  constexpr int NSLOT = NS + NP;   // MFMAs per step (NS == NP for D = 64 and 128)
+  constexpr int A_SLOTS = 5;       // slots that carry the max / threshold work
+  static_assert(NS == NP, "the slot pattern alternates one MFMA of each product");
+  float alpha, mx, msc_new, psum = 0.f;
+  bool grow;
+
+  // slot i = 2 m + w: w = 0 -> S^T MFMA number m, w = 1 -> O^T MFMA number m.
+  //   S^T MFMA m: key block m & 1, contraction step m >> 1 (the two accumulators alternate).
+  //   O^T MFMA m: key slice m / DB, row block m % DB (an accumulator comes back every DB MFMAs).
+  // The fragments of MFMA pair m+1 are read from LDS while pair m runs.
+  auto k_frag = [&](int m) { return lds_read_k(k_tile + (m & 1) * 32 * ROWB + (((2 * (m >> 1)) ^ kx2) << 4)); };
+  auto v_frag = [&](int m) {
+    return lds_read_vt(v_tile + (16 * (m / DB)) * ROWB + (((4 * (m % DB)) ^ vx2) << 4), 8 * ROWB);
+  };
+  bf16x8 kf[2], vf[2];
+  kf[0] = k_frag(0);
+  vf[0] = v_frag(0);
+  f32x16 zero;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) zero[r] = 0.f;
+
+#pragma unroll
+  for (int i = 0; i < NSLOT; ++i) {
+    const int m = i >> 1, w = i & 1, mb = m & 1;
+    if (w == 0 && m + 1 < NS) {
+      kf[mb ^ 1] = k_frag(m + 1);
+      vf[mb ^ 1] = v_frag(m + 1);
+    }
+    // ---- matrix pipe.  The empty asm statements order each MFMA against the vector slices around it (all asm
+    // volatile statements keep their relative order), which fixes the interleaving written here.
+    if (w == 0) {
+      const int kb = m & 1, kk = m >> 1;
+      asm volatile("" : "+v"(kf[mb]));
+      if (kk == 0) s_nxt[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[mb], qf[kk], zero, 0, 0, 0);
+      else s_nxt[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[mb], qf[kk], s_nxt[kb], 0, 0, 0);
+      asm volatile("" : "+v"(s_nxt[kb]));
+    } else {
+      const int ks = m / DB, db = m % DB;
+      asm volatile("" : "+v"(vf[mb]));
+      o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[mb], as_bf16x8(p_prev[ks]), o[db], 0, 0, 0);
+      asm volatile("" : "+v"(o[db]));
+    }
+    // ---- vector pipe slice
+    if (i < 4) {  // row maximum over a quarter of the tile's keys
+      const int kb = i >> 1, r0 = 8 * (i & 1);
+      float t = i ? mx : s_cur[0][0];
+      asm volatile("" : "+v"(t));
+#pragma unroll
+      for (int r = 0; r < 8; r += 2) t = fmaxf(fmaxf(t, s_cur[kb][r0 + r]), s_cur[kb][r0 + r + 1]);
+      mx = (i == 3) ? half_swap_max(t) : t;
+      asm volatile("" : "+v"(mx));
+    } else if (i == 4) {  // lazy running maximum (log2 domain), rescale factor
+      const float mxs = mx * sc;
+      grow = mxs > msc + kAtLazyLog2;
+      msc_new = grow ? mxs : msc;
+      alpha = __builtin_amdgcn_exp2f(msc - msc_new);
+      msc = msc_new;
+      asm volatile("" : "+v"(alpha), "+v"(msc_new));
+    } else {  // exponentials of the elements assigned to this slot
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {  // unit = two neighbouring keys of the query
+        if (A_SLOTS + (u * (NSLOT - A_SLOTS)) / 16 == i) {
+          const int kb = u >> 3, r = 2 * (u & 7);
+          float a0 = s_cur[kb][r], a1 = s_cur[kb][r + 1];
+          asm volatile("" : "+v"(a0), "+v"(a1));  // the slice may not rise above the previous MFMA ...
+          const float pe0 = __builtin_amdgcn_exp2f(fmaf(a0, sc, -msc_new));
+          const float pe1 = __builtin_amdgcn_exp2f(fmaf(a1, sc, -msc_new));
+          psum += pe0 + pe1;
+          unsigned pk = pack_bf16(pe0, pe1);
+          asm volatile("" : "+v"(pk), "+v"(psum));  // ... nor sink below the next one
+          p_cur[2 * kb + (r >> 3)][(r & 7) >> 1] = pk;
+        }
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  l_run = fmaf(l_run, alpha, psum);
+  // O^T now holds tiles < t scaled by the old maximum; bring it to the new one before tile t is added
+  if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+#pragma unroll
+    for (int b = 0; b < DB; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[b][r] *= alpha;
+  }
+}
+
+// Block mask / ragged tail for the tile starting at key0: register r of s[kb] holds key
+// key0 + 32 kb + 8 (r/4) + 4 g + (r%4).
+__device__ __forceinline__ void attn_mask(f32x16 (&s)[2], int key0, int lim, int g) {
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int kidx = key0 + 32 * kb + 8 * (r >> 2) + 4 * g + (r & 3);
+      if (kidx >= lim) s[kb][r] = -INFINITY;
+    }
+}
+
 template <int D, bool OUT_F32>
 __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnParams p) {
-  constexpr int ROWB = 2 * D;            // bytes per K/V row of one head
-  constexpr int TILEB = kAtBK * ROWB;    // bytes per K (or V) tile
-  constexpr int CH = D / 8;              // 16-byte chunks per row
-  constexpr int RPB = 256 / ROWB;        // rows per 256 bytes (one pass over all LDS banks)
-  constexpr int RPI = 1024 / ROWB;       // rows written by one wave-wide 16-byte-per-lane load
-  constexpr int LPT = TILEB / 1024 / kAtWaves;  // such loads per wave per tensor per tile
-  constexpr int KD = D / 16;             // contraction steps of S^T
-  constexpr int DB = D / 32;             // 32-row blocks of O^T
+  constexpr int ROWB = 2 * D;                  // bytes per K/V row of one head
+  constexpr int TILEB = kAtTileKeys * ROWB;    // bytes per K (or V) tile
+  constexpr int CH = D / 8;                    // 16-byte chunks per row
+  constexpr int RPB = 256 / ROWB;              // rows per 256 bytes (one pass over all LDS banks)
+  constexpr int RPI = 1024 / ROWB;             // rows written by one wave-wide 16-byte-per-lane load
+  constexpr int LPT = TILEB / 1024 / kAtWaves; // such loads per wave per tensor per tile
+  constexpr int KD = D / 16;
+  constexpr int DB = D / 32;
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds_raw[];
   lds_byte* const k_ring = (lds_byte*)lds_raw;
   lds_byte* const v_ring = k_ring + kAtStages * TILEB;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int group = wave >> 2;  // waves w and w+4 share a SIMD and alternate roles
   const int g = lane >> 5, c = lane & 31;
   const int h = blockIdx.y;
   const int i_first = blockIdx.x * kAtBQ;
   const int i_last = (i_first + kAtBQ - 1 < p.Lq) ? i_first + kAtBQ - 1 : p.Lq - 1;
-  const int q_row = i_first + wave * 32 + c;
-  const int qi = q_row < p.Lq ? q_row : p.Lq - 1;
   const int L_B = p.block_len;
   const int n_total = p.n_kept + p.Lc;
+  const long long head_off = (long long)h * D;
 
   // number of visible keys: per lane (its query) and the workgroup's extremes
   auto visible = [&](int i) {
     const int e = (i / L_B + 1) * L_B;
     return p.n_kept + (e < p.Lc ? e : p.Lc);
   };
-  const int lim = visible(qi);
+  const int q_row = i_first + wave * 32 + c;
+  const int lim = visible(q_row < p.Lq ? q_row : p.Lq - 1);
   const int lim_min = visible(i_first);
   const int lim_max = visible(i_last);
-  const int n_tiles = (lim_max + kAtBK - 1) / kAtBK;
+  const int n_tiles = (lim_max + kAtTileKeys - 1) / kAtTileKeys;  // key tiles this workgroup visits
+  const int n_iter = (n_tiles + 1) / 2;                           // two tiles per loop iteration
 
-  // ---- global -> LDS tile loads.  Load j of this wave fills LDS rows (wave + 8 j) * RPI .. + RPI of a
-  // tile; lane -> (row, slot); the slot receives chunk (slot ^ swizzle(row)) of that row.
+  // ---- global -> LDS tile loads.  Load j of this wave fills LDS rows (wave + W j) * RPI .. + RPI of a tile;
+  // lane -> (row, slot); the slot receives chunk (slot ^ swizzle(row)) of that row.
   int ld_row[LPT], ld_kchunk[LPT], ld_vchunk[LPT];
 #pragma unroll
   for (int j = 0; j < LPT; ++j) {
@@ -129,9 +269,8 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnPara
     ld_kchunk[j] = slot ^ ((row / RPB) & (CH - 1));
     ld_vchunk[j] = slot ^ (4 * ((row / RPB) & (CH / 4 - 1)));
   }
-  const long long head_off = (long long)h * D;
-  // one tensor's tile: rows past the end are masked later, so they read a valid row instead.  The chunk segment's
-  // base is pre-shifted by -n_kept rows so that both segments are addressed as base + key_index * stride.
+  // Rows past the end are masked later, so they read a valid row instead.  The chunk segment's base is
+  // pre-shifted by -n_kept rows so that both segments are addressed as base + key_index * stride.
   const long long ldc_b = p.ld_c * 2, ldn_b = p.ld_n * 2;
   auto issue_one = [&](int tile, const unsigned short* cache, const unsigned short* chunk, lds_byte* ring,
                        const int (&chunk_of)[LPT]) {
@@ -140,38 +279,40 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnPara
     const char* base_n = reinterpret_cast<const char*>(chunk + head_off) - (long long)p.n_kept * ldn_b;
 #pragma unroll
     for (int j = 0; j < LPT; ++j) {
-      int kidx = tile * kAtBK + ld_row[j];
+      int kidx = tile * kAtTileKeys + ld_row[j];
       kidx = kidx < n_total ? kidx : n_total - 1;
       const bool in_cache = kidx < p.n_kept;
-      const char* src = (in_cache ? base_c : base_n) + (unsigned long long)(unsigned)kidx * (unsigned long long)(in_cache ? ldc_b : ldn_b) + chunk_of[j] * 16;
+      const char* src = (in_cache ? base_c : base_n) +
+                        (unsigned long long)(unsigned)kidx * (unsigned long long)(in_cache ? ldc_b : ldn_b) +
+                        chunk_of[j] * 16;
       lds_byte* dst = ring + stage * TILEB + (wave + kAtWaves * j) * 1024;
       dma_row_chunks(src, __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)dst));
     }
   };
-  // K of tile kt and V of tile kt - 1 travel together (V is consumed one iteration after K)
-  auto issue_tile = [&](int kt) {
+  // Step t reads K tile t+1 and V tile t-1.  At its start K(t+S) and V(t+S-2) are issued into the slots of K(t)
+  // and V(t-2), whose last readers finished in step t-1.
+  auto issue_tiles = [&](int kt) {
     issue_one(kt, p.Kc, p.Kn, k_ring, ld_kchunk);
-    if (kt > 0) issue_one(kt - 1, p.Vc, p.Vn, v_ring, ld_vchunk);
+    if (kt >= 2) issue_one(kt - 2, p.Vc, p.Vn, v_ring, ld_vchunk);
   };
 
   // ---- LDS read offsets (bytes inside a tile)
-  // K fragment (A operand): lane (key row c, half g) reads chunk (2 kk + g) of row 32 kb + c
-  const int kx = (c / RPB) & (CH - 1);
+  // K fragment (A operand): lane (key row c, half g) reads chunk (2 kk + g) of row c; its slot is (2 kk) ^ kx2
+  const int kx2 = g ^ ((c / RPB) & (CH - 1));
   const int k_off = c * ROWB;
-  const int kx2 = g ^ kx;  // LDS slot of step kk is (2 kk) ^ kx2
-  // V^T fragment via transposing reads: 16-lane group = (d-half, key group g); lane i of the group points at
-  // key row rr = 4 g + i/4, four consecutive d at 4 (i%4)
+  // V^T fragment via transposing reads: 16-lane group = (d-half, key group g); lane i of the group points at key
+  // row rr = 4 g + i/4, four consecutive d at 4 (i%4).  32 lanes (one key group) read 4 rows x 64 bytes per
+  // instruction; the swizzle spreads those over all banks.  Slot of d-block b is ((4 b) ^ vx2) + cl.
   const int i16 = lane & 15;
   const int rr = 4 * g + (i16 >> 2);
-  // (32 lanes = one key group read 4 rows x 64 bytes per transposing read: the swizzle spreads them over all banks)
-  const int vx = 4 * ((rr / RPB) & (CH / 4 - 1));
+  const int vx2 = 4 * ((rr / RPB) & (CH / 4 - 1));
   const int cl = 2 * ((lane >> 4) & 1) + ((i16 & 3) >> 1);
   const int v_off = rr * ROWB + ((i16 & 1) << 3) + (cl << 4);
-  const int vx2 = vx;  // LDS slot of d-block b is ((4 b) ^ vx2) + cl
 
   // Q^T fragments (B operand): lane (query c, half g) holds Q[q][16 kk + 8 g .. +8]
   bf16x8 qf[KD];
   {
+    const int qi = q_row < p.Lq ? q_row : p.Lq - 1;
     const unsigned short* qp = p.Q + (long long)qi * p.ld_q + head_off + 8 * g;
 #pragma unroll
     for (int kk = 0; kk < KD; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(qp + 16 * kk);
@@ -182,128 +323,72 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnPara
   for (int b = 0; b < DB; ++b)
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[b][r] = 0.f;
-  f32x16 s[2];
-  bf16x8 pf[4];
-  float m_run = -INFINITY, l_run = 0.f;
+  f32x16 s_a[2], s_b[2];
+  u32x4 p_a[4], p_b[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { p_a[ks][e] = 0u; p_b[ks][e] = 0u; }
+  float msc = -INFINITY, l_run = 0.f;
   const float sc = p.scale_log2;
 
-  // matrix phase of iteration t: S^T(t) = K(t) Q^T  and  O^T += V(t-1)^T P(t-1)^T
-  auto matrix_phase = [&](int t) {
-    __builtin_amdgcn_s_setprio(1);
-    if (t < n_tiles) {
-      const lds_byte* kt = k_ring + (t % kAtStages) * TILEB + k_off;
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
-#pragma unroll
-      for (int kk = 0; kk < KD; ++kk) {
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {  // the two key blocks alternate: no back-to-back dependent MFMAs
-          const bf16x8 a =
-              *(const __attribute__((address_space(3))) bf16x8*)(kt + kb * 32 * ROWB + (((2 * kk) ^ kx2) << 4));
-          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], s[kb], 0, 0, 0);
-        }
-      }
-    }
-    if (t > 0) {
-      const lds_byte* vt = v_ring + ((t - 1) % kAtStages) * TILEB + v_off;
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-#pragma unroll
-        for (int b = 0; b < DB; ++b) {
-          const lds_byte* a0 = vt + (16 * ks) * ROWB + (((4 * b) ^ vx2) << 4);
-          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(a0));
-          const s16x4 hi =
-              __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(a0 + 8 * ROWB));
-          const s16x8 a16 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a16), pf[ks], o[b], 0, 0, 0);
-        }
-      }
-    }
-    __builtin_amdgcn_s_setprio(0);
-  };
+  auto k_addr = [&](int tile) { return k_ring + (tile % kAtStages) * TILEB + k_off; };
+  auto v_addr = [&](int tile) { return v_ring + (tile % kAtStages) * TILEB + v_off; };
 
-  // vector phase of iteration t: online softmax of S^T(t) -> P^T(t), rescale of O^T
-  auto vector_phase = [&](int t) {
-    if (t >= n_tiles) return;
-    // block mask / ragged tail: key index of register r is t*64 + 32 kb + 8 (r/4) + 4 g + (r%4)
-    if ((t + 1) * kAtBK > lim_min) {
+  // ---- prologue: fill the ring (K tiles 0..S-1, V tiles 0..S-3), then S^T(0)
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int kidx = t * kAtBK + 32 * kb + 8 * (r >> 2) + 4 * g + (r & 3);
-          if (kidx >= lim) s[kb][r] = -INFINITY;
-        }
-    }
-    float mx = s[0][0];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
-    mx = half_swap_max(mx);
-    const float m_new = fmaxf(m_run, mx);
-    const float msc = m_new * sc;
-    float psum = 0.f;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float pe = __builtin_amdgcn_exp2f(fmaf(s[kb][r], sc, -msc));
-        psum += pe;
-        pf[2 * kb + (r >> 3)][r & 7] = (__bf16)pe;
-      }
-    // the running maximum rarely moves after the first tiles: rescale only when some query's did
-    if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
-      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * sc);
-      l_run *= alpha;
-#pragma unroll
-      for (int b = 0; b < DB; ++b)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o[b][r] *= alpha;
-      m_run = m_new;
-    }
-    l_run += psum;
-  };
-
-  // ---- prologue: fill the ring (K tiles 0..S-2, V tiles 0..S-3), then run the phases.
-  // Even phase 2t: every wave issues K(t+S-1) and V(t+S-2) into the slots whose tiles (K(t-1), V(t-2)) were last
-  // read in phase 2t-1; group 0 runs matrix(t), group 1 runs vector(t-1).
-  // Odd phase 2t+1: group 0 runs vector(t), group 1 runs matrix(t); before its closing barrier every wave waits
-  // until only the loads of the last S-2 even phases are still in flight (K(t+1) and V(t) have landed).
-#pragma unroll
-  for (int u = 0; u < kAtStages - 1; ++u) issue_tile(u);  // tiles past the end hold clamped rows, never read back
+  for (int u = 0; u < kAtStages; ++u) issue_tiles(u);  // tiles past the end hold clamped rows, never read back
   wait_vmcnt<0>();
   __builtin_amdgcn_s_barrier();
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s_a[kb][r] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < KD; ++kk) {
+      const bf16x8 a = lds_read_k(k_addr(0) + kb * 32 * ROWB + (((2 * kk) ^ kx2) << 4));
+      s_a[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], s_a[kb], 0, 0, 0);
+    }
+  }
 
-  const int n_iter = n_tiles + 1;  // matrix(t) for t = 0..n_tiles (the last one only updates O^T)
-  if (group == 0) {
+  // Step t: S^T(t+1) into the "next" registers, softmax of S^T(t), O^T += tile t-1.  Iteration T runs step 2T
+  // (s_a -> p_a, next into s_b, adds p_b) and step 2T+1 (s_b -> p_b, next into s_a, adds p_a).  The tile count is
+  // padded to even: a tile past the end is fully masked and contributes nothing.  Before the first tile p_b is
+  // zero, and when there is no next tile the S^T product re-reads the current one (its result is never used).
+  // After each step: K(t+2) and V(t) must have landed before the next step; only the loads of the last two steps
+  // may stay in flight.
 #pragma unroll 1
-    for (int t = 0; t < n_iter; ++t) {
-      issue_tile(t + kAtStages - 1);
-      matrix_phase(t);
-      __builtin_amdgcn_s_barrier();
-      vector_phase(t);
-      wait_vmcnt<2 * LPT*(kAtStages - 2)>();
+  for (int T = 0; T < n_iter; ++T) {
+    {
+      const int t = 2 * T;
+      issue_tiles(t + kAtStages);
+      if ((t + 1) * kAtTileKeys > lim_min) attn_mask(s_a, t * kAtTileKeys, lim, g);
+      attn_step<D>(s_a, s_b, p_b, p_a, o, qf, msc, l_run, k_addr(t + 1), v_addr(t > 0 ? t - 1 : 0), kx2, vx2, sc);
+      wait_vmcnt<2 * 2 * LPT>();
       __builtin_amdgcn_s_barrier();
     }
-  } else {
-#pragma unroll 1
-    for (int t = 0; t < n_iter; ++t) {
-      issue_tile(t + kAtStages - 1);
-      if (t > 0) vector_phase(t - 1);
+    {
+      const int t = 2 * T + 1;
+      issue_tiles(t + kAtStages);
+      if ((t + 1) * kAtTileKeys > lim_min) attn_mask(s_b, t * kAtTileKeys, lim, g);
+      attn_step<D>(s_b, s_a, p_a, p_b, o, qf, msc, l_run, k_addr(T + 1 < n_iter ? t + 1 : t), v_addr(t - 1), kx2, vx2, sc);
+      wait_vmcnt<2 * 2 * LPT>();
       __builtin_amdgcn_s_barrier();
-      matrix_phase(t);
-      wait_vmcnt<2 * LPT*(kAtStages - 2)>();
-      __builtin_amdgcn_s_barrier();
+    }
+  }
+  // the last tile's contribution
+  {
+    const lds_byte* vt = v_addr(2 * n_iter - 1);
+#pragma unroll
+    for (int m = 0; m < 4 * DB; ++m) {
+      const bf16x8 a = lds_read_vt(vt + (16 * (m / DB)) * ROWB + (((4 * (m % DB)) ^ vx2) << 4), 8 * ROWB);
+      o[m % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, as_bf16x8(p_b[m / DB]), o[m % DB], 0, 0, 0);
     }
   }
   wait_vmcnt<0>();  // nothing may still be writing this workgroup's LDS when it retires
 
   // normalise and store: lane holds query c, d = 32 b + 8 (r/4) + 4 g + (r%4)
-  const float l_tot = half_swap_sum(l_run);
-  const float inv = 1.0f / l_tot;
+  const float inv = 1.0f / half_swap_sum(l_run);
   if (q_row < p.Lq) {
 #pragma unroll
     for (int b = 0; b < DB; ++b)
