@@ -192,7 +192,8 @@ __device__ __forceinline__ void attn_step(const f32x16 (&s_cur)[2], f32x16 (&s_n
           asm volatile("" : "+v"(a0), "+v"(a1));  // the slice may not rise above the previous MFMA ...
           const float pe0 = __builtin_amdgcn_exp2f(fmaf(a0, sc, -msc_new));
           const float pe1 = __builtin_amdgcn_exp2f(fmaf(a1, sc, -msc_new));
-          psum += pe0 + pe1;
+          psum += pe0;
+          psum += pe1;
           unsigned pk = pack_bf16(pe0, pe1);
           asm volatile("" : "+v"(pk), "+v"(psum));  // ... nor sink below the next one
           p_cur[2 * kb + (r >> 3)][(r & 7) >> 1] = pk;
@@ -259,41 +260,59 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnPara
   const int n_iter = (n_tiles + 1) / 2;                           // two tiles per loop iteration
 
   // ---- global -> LDS tile loads.  Load j of this wave fills LDS rows (wave + W j) * RPI .. + RPI of a tile;
-  // lane -> (row, slot); the slot receives chunk (slot ^ swizzle(row)) of that row.
-  int ld_row[LPT], ld_kchunk[LPT], ld_vchunk[LPT];
+  // lane -> (row, slot); the slot receives chunk (slot ^ swizzle(row)) of that row.  Rows past the end are masked
+  // later, so they read a valid row instead.  The chunk segment's base is pre-shifted by -n_kept rows so that both
+  // segments are addressed as base + key_index * stride.  A tile that lies inside one segment (all but one or two)
+  // needs only a scalar tile base plus a per-lane byte offset prepared here.
+  const long long ldc_b = p.ld_c * 2, ldn_b = p.ld_n * 2;
+  unsigned k_offc[LPT], k_offn[LPT], v_offc[LPT], v_offn[LPT];
 #pragma unroll
   for (int j = 0; j < LPT; ++j) {
     const int row = (wave + kAtWaves * j) * RPI + lane / CH;
     const int slot = lane % CH;
-    ld_row[j] = row;
-    ld_kchunk[j] = slot ^ ((row / RPB) & (CH - 1));
-    ld_vchunk[j] = slot ^ (4 * ((row / RPB) & (CH / 4 - 1)));
+    const int kch = slot ^ ((row / RPB) & (CH - 1));
+    const int vch = slot ^ (4 * ((row / RPB) & (CH / 4 - 1)));
+    k_offc[j] = (unsigned)(row * ldc_b) + kch * 16;
+    k_offn[j] = (unsigned)(row * ldn_b) + kch * 16;
+    v_offc[j] = (unsigned)(row * ldc_b) + vch * 16;
+    v_offn[j] = (unsigned)(row * ldn_b) + vch * 16;
   }
-  // Rows past the end are masked later, so they read a valid row instead.  The chunk segment's base is
-  // pre-shifted by -n_kept rows so that both segments are addressed as base + key_index * stride.
-  const long long ldc_b = p.ld_c * 2, ldn_b = p.ld_n * 2;
   auto issue_one = [&](int tile, const unsigned short* cache, const unsigned short* chunk, lds_byte* ring,
-                       const int (&chunk_of)[LPT]) {
+                       const unsigned (&offc)[LPT], const unsigned (&offn)[LPT], bool is_v) {
     const int stage = tile % kAtStages;
+    const int key0 = tile * kAtTileKeys;
     const char* base_c = reinterpret_cast<const char*>(cache + head_off);
     const char* base_n = reinterpret_cast<const char*>(chunk + head_off) - (long long)p.n_kept * ldn_b;
+    const bool all_cache = key0 + kAtTileKeys <= p.n_kept;
+    const bool all_chunk = key0 >= p.n_kept && key0 + kAtTileKeys <= n_total;
+    if (all_cache || all_chunk) {  // workgroup-uniform
+      const char* tile_base = all_cache ? base_c + (long long)key0 * ldc_b : base_n + (long long)key0 * ldn_b;
 #pragma unroll
-    for (int j = 0; j < LPT; ++j) {
-      int kidx = tile * kAtTileKeys + ld_row[j];
-      kidx = kidx < n_total ? kidx : n_total - 1;
-      const bool in_cache = kidx < p.n_kept;
-      const char* src = (in_cache ? base_c : base_n) +
-                        (unsigned long long)(unsigned)kidx * (unsigned long long)(in_cache ? ldc_b : ldn_b) +
-                        chunk_of[j] * 16;
-      lds_byte* dst = ring + stage * TILEB + (wave + kAtWaves * j) * 1024;
-      dma_row_chunks(src, __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)dst));
+      for (int j = 0; j < LPT; ++j) {
+        lds_byte* dst = ring + stage * TILEB + (wave + kAtWaves * j) * 1024;
+        dma_row_chunks(tile_base + (all_cache ? offc[j] : offn[j]), __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)dst));
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < LPT; ++j) {
+        const int row = (wave + kAtWaves * j) * RPI + lane / CH;
+        const int slot = lane % CH;
+        const int ch = is_v ? slot ^ (4 * ((row / RPB) & (CH / 4 - 1))) : slot ^ ((row / RPB) & (CH - 1));
+        int kidx = key0 + row;
+        kidx = kidx < n_total ? kidx : n_total - 1;
+        const bool in_cache = kidx < p.n_kept;
+        const char* src = (in_cache ? base_c : base_n) +
+                          (unsigned long long)(unsigned)kidx * (unsigned long long)(in_cache ? ldc_b : ldn_b) + ch * 16;
+        lds_byte* dst = ring + stage * TILEB + (wave + kAtWaves * j) * 1024;
+        dma_row_chunks(src, __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)dst));
+      }
     }
   };
   // Step t reads K tile t+1 and V tile t-1.  At its start K(t+S) and V(t+S-2) are issued into the slots of K(t)
   // and V(t-2), whose last readers finished in step t-1.
   auto issue_tiles = [&](int kt) {
-    issue_one(kt, p.Kc, p.Kn, k_ring, ld_kchunk);
-    if (kt >= 2) issue_one(kt - 2, p.Vc, p.Vn, v_ring, ld_vchunk);
+    issue_one(kt, p.Kc, p.Kn, k_ring, k_offc, k_offn, false);
+    if (kt >= 2) issue_one(kt - 2, p.Vc, p.Vn, v_ring, v_offc, v_offn, true);
   };
 
   // ---- LDS read offsets (bytes inside a tile)
