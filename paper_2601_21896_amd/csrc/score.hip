@@ -21,6 +21,7 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+__device__ __forceinline__ bf16x8 as_bf16x8(const u32x4& v) { return __builtin_bit_cast(bf16x8, v); }
 
 __device__ __forceinline__ float bf16_bits_to_f32(unsigned short b) { return __uint_as_float((uint32_t)b << 16); }
 
@@ -214,6 +215,204 @@ __global__ __launch_bounds__(kScThreads, 2) void score_mfma_kernel(const unsigne
   if (g == 0 && tok < T) out[tok] = partial + (b2bar ? *b2bar : 0.f);
 }
 
+// ---------------------------------------------------------------------------------- streaming MFMA path
+// For M % 256 == 0 and Fs % 64 == 0.  With a 256-wide hidden layer the head sits near the ridge of the roofline
+// (about 256 flop per byte of features), and every CU has to pull all of W1 through its L1 once per token group, so
+// the kernel must keep the matrix cores and the memory pipe busy at the same time: an even spread of MFMA work over
+// the 1024 SIMDs, few LDS bytes per MFMA, and many bytes in flight without spending registers on them.
+//  - A workgroup owns TT 32-token tiles (TT picked at launch so that the grid needs as few rounds over the 256 CUs
+//    as possible) and one 256-unit pass of the hidden layer at a time.  Its 8 waves split the hidden units four
+//    ways and the reduction axis two ways: wave (hq, kh) accumulates hidden units [64 hq, 64 hq + 64) for all TT
+//    tiles over half of the k-steps of every slab, so one W1 fragment feeds TT MFMAs and one feature fragment two.
+//    The two reduction halves sit on the same SIMD (waves w and w + 4) and are added through LDS at the end of a pass.
+//  - W1 and the features stream global -> LDS with global_load_lds through a ring of slabs (no staging registers,
+//    all but one slab of the ring in flight), rows XOR-swizzled in 16-byte chunks for conflict-free b128 reads.
+constexpr int kS3Slab = 64;                      // features per slab (full 128-byte lines per row)
+constexpr int kS3RowB = kS3Slab * 2;             // bytes per slab row
+constexpr int kS3Chunks = kS3RowB / 16;          // 16-byte chunks per row
+constexpr int kS3RowsPerLoad = 1024 / kS3RowB;   // rows covered by one wave-wide 16-byte-per-lane load
+constexpr int kS3Stages = 3;                     // ring depth: 3 x (32 KB + 4 TT KB) <= 156 KB
+constexpr int kS3WBytes = 256 * kS3RowB;         // W1 part of a stage (256 hidden units)
+constexpr int kS3MaxTT = 5;
+constexpr int kS3RedBytes = 65536;               // two 32 KB regions for the end-of-pass reduction
+constexpr int s3_stage_bytes(int TT) { return kS3WBytes + 32 * TT * kS3RowB; }
+constexpr int s3_lds_bytes(int TT) {
+  return kS3Stages * s3_stage_bytes(TT) > kS3RedBytes ? kS3Stages * s3_stage_bytes(TT) : kS3RedBytes;
+}
+// chunk q of row r lives in slot q ^ swz(r): 16 consecutive rows of one chunk then cover all 64 banks
+__device__ __forceinline__ int s3_swz(int row) {
+  return kS3RowB == 64 ? (row >> 2) & 3 : (row >> 1) & 7;
+}
+
+// 64 x 16 bytes global -> LDS: lane l's bytes at (uniform base + its byte offset) land at lds_addr + 16 l
+__device__ __forceinline__ void s3_dma(const void* base_uniform, unsigned byte_off, unsigned lds_addr_uniform) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(lds_addr_uniform), "v"(byte_off), "s"(base_uniform)
+               : "memory");
+}
+template <int N>
+__device__ __forceinline__ void s3_wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+template <int TT>
+__global__ __launch_bounds__(512, 1) void score_stream_kernel(
+    const unsigned short* __restrict__ x0, const unsigned short* __restrict__ x1, const unsigned short* __restrict__ x2,
+    int T, int Fs, int F, long long ld_x, const unsigned short* __restrict__ W1, const float* __restrict__ b1,
+    const float* __restrict__ w2bar, const float* __restrict__ b2bar, int M, int act, float* __restrict__ out) {
+  constexpr int kStageB = s3_stage_bytes(TT);
+  constexpr int WU = 256 / kS3RowsPerLoad;             // wave-wide loads that fill the W1 part of a stage
+  constexpr int XU = 32 * TT / kS3RowsPerLoad;         // ... and the feature part
+  constexpr int LW = WU / 8;                           // W1 loads per wave per slab
+  constexpr int LX = (XU + 7) / 8;                     // feature loads per wave per slab
+  constexpr int LPW = LW + LX;
+  constexpr int KS = kS3Slab / 32;                     // k-steps (16 features) per wave per slab
+  typedef __attribute__((address_space(3))) unsigned char lds_byte;
+  typedef __attribute__((address_space(3))) bf16x8 lds_frag;
+  typedef float f32x4_t __attribute__((ext_vector_type(4)));
+  typedef __attribute__((address_space(3))) f32x4_t lds_f4;
+  extern __shared__ __attribute__((aligned(1024))) unsigned char lds_raw[];
+  lds_byte* const ring = (lds_byte*)lds_raw;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int hq = wave & 3, kh = wave >> 2;
+  const int g = lane >> 5, c = lane & 31;
+  const int tok_base = blockIdx.x * (32 * TT);
+  const int n_slabs = F / kS3Slab;
+  const int slabs_per_seg = Fs / kS3Slab;
+
+  // ---- loads.  One wave-wide load covers kS3RowsPerLoad slab rows: lane -> (row, LDS slot); the slot receives chunk
+  // slot ^ swz(row) of the row.  Addresses are a uniform base plus a 32-bit per-lane byte offset.  Surplus feature
+  // loads repeat a unit (same bytes, same place) so that every wave issues the same number of loads.
+  const int d_row = lane / kS3Chunks, d_slot = lane % kS3Chunks;
+  unsigned w_off[LW], x_off[LX];
+#pragma unroll
+  for (int j = 0; j < LW; ++j) {
+    const int row = (wave + 8 * j) * kS3RowsPerLoad + d_row;
+    w_off[j] = (unsigned)((row * F + (d_slot ^ s3_swz(row)) * 8) * 2);
+  }
+#pragma unroll
+  for (int j = 0; j < LX; ++j) {
+    const int row = ((wave + 8 * j) % XU) * kS3RowsPerLoad + d_row;
+    const int rel = tok_base + row < T ? row : T - 1 - tok_base;
+    x_off[j] = (unsigned)(rel * ld_x * 2) + (d_slot ^ s3_swz(row)) * 16;
+  }
+  const long long x_wg_off = (long long)tok_base * ld_x;
+  // ---- fragment reads inside a stage: k-step ks = KS kh + j of the slab, lane half g -> chunk 2 ks + g.
+  // swz(row) only depends on c for the rows a lane reads (row = 32-row block + c).
+  int rd[KS];
+#pragma unroll
+  for (int j = 0; j < KS; ++j) rd[j] = c * kS3RowB + (((2 * (KS * kh + j) + g) ^ s3_swz(c)) << 4);
+
+  float partial[TT];
+#pragma unroll
+  for (int tt = 0; tt < TT; ++tt) partial[tt] = 0.f;
+
+#pragma unroll 1
+  for (int mp = 0; mp < M; mp += 256) {
+    f32x16 acc[TT][2];
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[tt][b][r] = 0.f;
+    const unsigned short* const w_pass = W1 + (long long)mp * F;  // uniform
+
+    // slab S -> stage S % kS3Stages (slabs past the end re-read the last one; they are never consumed)
+#define PAFU_S3_ISSUE(S)                                                                                        \
+  do {                                                                                                          \
+    const int s_ = (S);                                                                                         \
+    const int sc_ = s_ < n_slabs ? s_ : n_slabs - 1;                                                            \
+    lds_byte* st_ = ring + (s_ % kS3Stages) * kStageB;                                                          \
+    _Pragma("unroll") for (int j = 0; j < LW; ++j)                                                              \
+        s3_dma(w_pass + sc_ * kS3Slab, w_off[j],                                                                \
+               __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(st_ + (wave + 8 * j) * 1024)));             \
+    const int seg_ = sc_ / slabs_per_seg;                                                                       \
+    const int fo_ = (sc_ - seg_ * slabs_per_seg) * kS3Slab;                                                     \
+    const unsigned short* xs_ = seg_ == 0 ? x0 : (seg_ == 1 ? x1 : x2);                                         \
+    _Pragma("unroll") for (int j = 0; j < LX; ++j)                                                              \
+        s3_dma(xs_ + x_wg_off + fo_, x_off[j], __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(            \
+                                                   st_ + kS3WBytes + ((wave + 8 * j) % XU) * 1024)));           \
+  } while (0)
+
+    __syncthreads();  // every wave is done with the LDS contents of the previous pass
+#pragma unroll
+    for (int s = 0; s < kS3Stages - 1; ++s) PAFU_S3_ISSUE(s);
+#pragma unroll 1
+    for (int s = 0; s < n_slabs; ++s) {
+      // slab s was issued kS3Stages - 1 iterations ago: only the loads of the younger slabs may still be in flight
+      s3_wait_vmcnt<(kS3Stages - 2) * LPW>();
+      __builtin_amdgcn_s_barrier();  // slab s visible to all; everyone is done reading slab s-1
+      PAFU_S3_ISSUE(s + kS3Stages - 1);  // into the stage slab s-1 just vacated
+      const lds_byte* st = ring + (s % kS3Stages) * kStageB;
+#pragma unroll
+      for (int j = 0; j < KS; ++j) {
+        const bf16x8 a0 = *(const lds_frag*)(st + (hq * 64) * kS3RowB + rd[j]);
+        const bf16x8 a1 = *(const lds_frag*)(st + (hq * 64 + 32) * kS3RowB + rd[j]);
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+          const bf16x8 xf = *(const lds_frag*)(st + kS3WBytes + tt * 32 * kS3RowB + rd[j]);
+          acc[tt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, xf, acc[tt][0], 0, 0, 0);
+          acc[tt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, xf, acc[tt][1], 0, 0, 0);
+        }
+      }
+    }
+#undef PAFU_S3_ISSUE
+    // ---- add the two halves of the reduction axis: wave (hq, 1) hands its accumulators to wave (hq, 0) through LDS,
+    // one token tile at a time, alternating between two 32 KB regions so that one barrier per tile is enough.
+    s3_wait_vmcnt<0>();
+    __syncthreads();  // all loads have landed and all fragment reads are done: the ring can be reused
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) {
+      lds_f4* reg = (lds_f4*)(ring + (tt & 1) * 32768) + hq * 8 * 64 + lane;
+      if (kh == 1) {
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            reg[(b * 4 + q) * 64] =
+                f32x4_t{acc[tt][b][4 * q], acc[tt][b][4 * q + 1], acc[tt][b][4 * q + 2], acc[tt][b][4 * q + 3]};
+      }
+      __syncthreads();
+      if (kh == 0) {
+        // activation and second layer; the lane holds token c of tile tt and hidden units
+        // mp + 64 hq + 32 b + 8 q + 4 g + e
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const f32x4_t o = reg[(b * 4 + q) * 64];
+            const int m0 = mp + 64 * hq + 32 * b + 8 * q + 4 * g;
+            const float4 w = *reinterpret_cast<const float4*>(w2bar + m0);
+            float4 bb = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (b1 != nullptr) bb = *reinterpret_cast<const float4*>(b1 + m0);
+            const float ov[4] = {o.x, o.y, o.z, o.w}, wv[4] = {w.x, w.y, w.z, w.w}, bv[4] = {bb.x, bb.y, bb.z, bb.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float h = acc[tt][b][4 * q + e] + ov[e] + bv[e];
+              partial[tt] = fmaf(wv[e], act == PAFU_ACT_SILU ? fast_silu(h) : act_accurate(h, act), partial[tt]);
+            }
+          }
+      }
+    }
+  }
+  // ---- add the two lane halves, then the four hidden quarters
+  __syncthreads();
+  float* red = reinterpret_cast<float*>(lds_raw);
+#pragma unroll
+  for (int tt = 0; tt < TT; ++tt) {
+    partial[tt] += __shfl_xor(partial[tt], 32);
+    if (kh == 0 && g == 0) red[hq * (32 * TT) + tt * 32 + c] = partial[tt];
+  }
+  __syncthreads();
+  for (int i = tid; i < 32 * TT; i += 512) {
+    const int tok = tok_base + i;
+    if (tok < T)
+      out[tok] = red[i] + red[32 * TT + i] + red[2 * 32 * TT + i] + red[3 * 32 * TT + i] + (b2bar ? *b2bar : 0.f);
+  }
+}
+
 }  // namespace
 
 int launch_score(hipStream_t st, const void* x0, const void* x1, const void* x2, int n_seg, int T, int Fs,
@@ -249,7 +448,45 @@ int launch_score(hipStream_t st, const void* x0, const void* x1, const void* x2,
                        static_cast<const unsigned short*>(x2), T, Fs, F, ld_x, static_cast<const unsigned short*>(W1), \
                        b1, w2bar, b2bar, M, act, out);                                                               \
   } while (0)
-    if (blocks % 8 == 0) PAFU_SCORE_CASE(8);
+    // the streaming kernel addresses rows by 32-bit byte offsets from a per-workgroup base
+    const bool offsets_fit = 32ll * kS3MaxTT * ld_x * 2 < (1ll << 31) && 256ll * F * 2 < (1ll << 31);
+    if (blocks % 8 == 0 && Fs % 64 == 0 && offsets_fit) {
+      // streaming kernel: TT 32-token tiles per workgroup.  Per 32 features a SIMD spends about 128 TT cycles in
+      // MFMAs and the CU about 64 (TT + 2) cycles serving fragment reads; each slab adds a fixed cost for the barrier
+      // and the exposed first reads.  Pick the TT that minimises that times the number of rounds the grid needs
+      // over the 256 CUs (ties go to the larger TT).
+      const int tiles = (T + 31) / 32;
+      int best_tt = 1;
+      long long best_cost = 1ll << 60;
+      for (int tt = 1; tt <= kS3MaxTT; ++tt) {
+        const int wgs = (tiles + tt - 1) / tt;
+        const int mfma = 128 * tt, lds = 64 * (tt + 2);
+        const long long cost = (long long)((wgs + 255) / 256) * ((kS3Slab / 32) * (mfma > lds ? mfma : lds) + 100);
+        if (cost <= best_cost) { best_cost = cost; best_tt = tt; }
+      }
+#define PAFU_SCORE3_CASE(TT)                                                                                         \
+  do {                                                                                                               \
+    static bool attr_set3 = false;                                                                                   \
+    if (!attr_set3) {                                                                                                \
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(score_stream_kernel<TT>),                     \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, s3_lds_bytes(TT));              \
+      if (e != hipSuccess) return record_hip_error(e);                                                               \
+      attr_set3 = true;                                                                                              \
+    }                                                                                                                \
+    hipLaunchKernelGGL(score_stream_kernel<TT>, dim3((tiles + TT - 1) / TT), dim3(512), s3_lds_bytes(TT), st,        \
+                       static_cast<const unsigned short*>(x0), static_cast<const unsigned short*>(x1),               \
+                       static_cast<const unsigned short*>(x2), T, Fs, F, ld_x, static_cast<const unsigned short*>(W1), \
+                       b1, w2bar, b2bar, M, act, out);                                                               \
+  } while (0)
+      switch (best_tt) {
+        case 1: PAFU_SCORE3_CASE(1); break;
+        case 2: PAFU_SCORE3_CASE(2); break;
+        case 3: PAFU_SCORE3_CASE(3); break;
+        case 4: PAFU_SCORE3_CASE(4); break;
+        default: PAFU_SCORE3_CASE(5); break;
+      }
+#undef PAFU_SCORE3_CASE
+    } else if (blocks % 8 == 0) PAFU_SCORE_CASE(8);
     else if (blocks % 4 == 0) PAFU_SCORE_CASE(4);
     else if (blocks % 2 == 0) PAFU_SCORE_CASE(2);
     else PAFU_SCORE_CASE(1);

@@ -132,6 +132,9 @@ def _score_case(cfg, T, bias, n_out, act, seed, n_seg=1):
     ("C1", 300, True, 1, "gelu_erf", 1),
     ("C1", 200, True, 12, "silu", 3),          # paper-form input [Q|K|V] (F = 4608)
     ("C4", 200, True, 1, "silu", 1),           # M = 512: two hidden passes
+    ("C1", 9601, True, 1, "silu", 1),          # streaming kernel with 2 token tiles per workgroup, ragged tail
+    ("C1", 20011, False, 1, "silu", 1),        # ... with 3
+    ("C1", 30000, True, 12, "silu", 3),        # ... with 4, three feature segments
 ])
 def test_score_matches_oracle(name, T, bias, n_out, act, n_seg):
     cfg = wl.CONFIGS[name]
@@ -165,6 +168,22 @@ def test_score_paper_true_width_mfma():
     torch.cuda.synchronize()
     want = orc.smlp_score(np.concatenate(segs, axis=1), W1, b1, W2, b2)
     assert np.abs(host(out) - want).max() < SCORE_MAX_ABS
+
+
+def test_score_mfma_path_with_hidden_width_not_a_multiple_of_256():
+    # bf16, F % 64 == 0, M % 32 == 0 but M % 256 != 0: the one-tile MFMA kernel
+    rng = np.random.default_rng(11)
+    T, F, M = 301, 192, 96
+    X = wl.round_to_bf16(rng.standard_normal((T, F)).astype(np.float32))
+    W1 = wl.round_to_bf16((rng.standard_normal((M, F)) * 0.1).astype(np.float32))
+    W2 = rng.standard_normal((3, M)).astype(np.float32)
+    b1 = rng.standard_normal(M).astype(np.float32)
+    b2 = rng.standard_normal(3).astype(np.float32)
+    out = torch.empty(T, device=DEV)
+    ws = torch.empty(M + 8, device=DEV)
+    B.pafu_score(dev(X, "bf16"), dev(W1, "bf16"), dev(b1), dev(W2), dev(b2), out, workspace=ws)
+    torch.cuda.synchronize()
+    assert np.abs(host(out) - orc.smlp_score(X, W1, b1, W2, b2)).max() < SCORE_MAX_ABS
 
 
 def test_score_generic_path_on_odd_shapes():
