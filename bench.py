@@ -212,6 +212,9 @@ def main():
                                            cur["O"]),
         )
 
+    # The repetitions are enqueued back to back, like the timed steps above, and read after one synchronisation at
+    # the end, so that the stage durations are taken at the same sustained clocks as the whole-step figure.
+    recorded = []
     for i in range(reps + 2):
         for cur in (sets if n_layers > 1 else [sets[i % n_sets]]):
             evs = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
@@ -220,10 +223,12 @@ def main():
             for j, c in enumerate(calls):
                 c()
                 evs[j + 1].record()
-            torch.cuda.synchronize()
             if i >= 2:
-                for j, s in enumerate(stage_names):
-                    stage_ms[s].append(evs[j].elapsed_time(evs[j + 1]))
+                recorded.append(evs)
+    torch.cuda.synchronize()
+    for evs in recorded:
+        for j, s in enumerate(stage_names):
+            stage_ms[s].append(evs[j].elapsed_time(evs[j + 1]))
     avg = {s: float(np.mean(v)) for s, v in stage_ms.items()}
     mn = {s: float(np.min(v)) for s, v in stage_ms.items()}
 
