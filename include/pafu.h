@@ -88,6 +88,14 @@ size_t pafu_select_workspace_bytes(int n);
 int pafu_select_topk(void* stream, const float* scores, int n, int k, int* out_ids, int* out_count,
                      void* workspace, size_t workspace_bytes);
 
+/* pafu_select_topk_pinned - the same retention with a frame sink (Sec. 4 "Experimental Implementation"; the
+ * frame-sink ablation): tokens [0, n_pinned) are never evicted and count towards the budget, i.e. they rank above
+ * every score (lower index first among themselves); the other k - n_pinned places go to the most salient of the
+ * remaining tokens.  k < n_pinned keeps tokens [0, k).  n_pinned = 0 is pafu_select_topk; n_pinned < 0 is an error.
+ */
+int pafu_select_topk_pinned(void* stream, const float* scores, int n, int k, int n_pinned, int* out_ids,
+                            int* out_count, void* workspace, size_t workspace_bytes);
+
 /* ------------------------------------------------------------------------------------------
  * pafu_compact_kv - cache update KV <- Select(KV; ids), SL <- Select(SL; ids), Alg. 2.
  *
@@ -166,6 +174,7 @@ typedef struct pafu_step_args {
   float* SL_out;       /* [min(k,n) (+ Lc in ROLLOUT)] out */
   void* O;             /* [Lc, N, D] out */
   void* workspace; size_t workspace_bytes; /* >= pafu_step_workspace_bytes(args) */
+  int n_pinned;        /* frame sink: cached tokens [0, n_pinned) are never evicted (0 = none) */
 } pafu_step_args;
 
 size_t pafu_step_workspace_bytes(const pafu_step_args* args /* host */);

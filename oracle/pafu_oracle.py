@@ -82,7 +82,7 @@ def smlp_score(X, W1, b1, W2, b2, act: str = "silu") -> np.ndarray:
 # --------------------------------------------------------------------------------------
 # Top-k retention
 # --------------------------------------------------------------------------------------
-def select_topk(scores_f32, k: int) -> np.ndarray:
+def select_topk(scores_f32, k: int, n_pinned: int = 0) -> np.ndarray:
     """Indices of the k most salient tokens, ascending.
 
     Sec. 3.4 (inference paragraph) and Alg. 2: keep the top-k of the score list.
@@ -91,15 +91,28 @@ def select_topk(scores_f32, k: int) -> np.ndarray:
     happens once the cache exceeds its budget).  The decision is taken on the fp32
     score values exactly as given.
 
+    n_pinned (frame sink, Sec. 4 "Experimental Implementation" and the frame-sink
+    ablation): the first n_pinned tokens of the cache are never evicted and count
+    towards the budget.  The retained set is that prefix plus the k - n_pinned most
+    salient of the other tokens; a budget smaller than the prefix keeps the first k
+    tokens of it.  The paper takes the mechanism from prior work without describing
+    it; this is the reading taken here.
+
     returns int32 [min(k, n)], sorted ascending.
     """
     s = np.asarray(scores_f32, dtype=np.float32)
     assert s.ndim == 1
     n = s.shape[0]
     k = int(k)
+    n_pinned = max(0, min(int(n_pinned), n))
     assert k >= 0
     if k >= n:
         return np.arange(n, dtype=np.int32)
+    if n_pinned >= k:
+        return np.arange(k, dtype=np.int32)
+    if n_pinned > 0:
+        rest = select_topk(s[n_pinned:], k - n_pinned) + n_pinned
+        return np.concatenate([np.arange(n_pinned, dtype=np.int32), rest.astype(np.int32)])
     isnan = np.isnan(s)
     val = s.astype(np.float64)
     val = np.where(isnan, 0.0, val) + 0.0  # x + 0.0 turns -0.0 into +0.0
@@ -181,7 +194,7 @@ def chunk_attention(Q, Kc, Vc, Kn, Vn, block_len: int, scale: float | None = Non
 # One chunk step
 # --------------------------------------------------------------------------------------
 def step_single(X_cache, X_chunk, W1, b1, W2, b2, K_cache, V_cache, Q, K_chunk, V_chunk,
-                k: int, block_len: int, act: str = "silu", forced_scores_f32=None):
+                k: int, block_len: int, act: str = "silu", forced_scores_f32=None, n_pinned: int = 0):
     """One step in SINGLE mode: score cached and new tokens, select the top-k cached
     tokens on the fresh cache scores, compact, attend (Alg. 2 order of operations;
     Sec. 3.4).
@@ -197,7 +210,7 @@ def step_single(X_cache, X_chunk, W1, b1, W2, b2, K_cache, V_cache, Q, K_chunk, 
     s_chunk = smlp_score(X_chunk, W1, b1, W2, b2, act)
     s = np.concatenate([s_cache, s_chunk])
     s32 = s.astype(np.float32) if forced_scores_f32 is None else np.asarray(forced_scores_f32, np.float32)
-    ids = select_topk(s32[:n], k)
+    ids = select_topk(s32[:n], k, n_pinned)
     Kk, Vk, SLk = compact_kv(K_cache, V_cache, s32[:n], ids)
     O = chunk_attention(Q, Kk, Vk, K_chunk, V_chunk, block_len)
     return dict(scores=s, ids=ids, K_kept=Kk, V_kept=Vk, SL_kept=SLk, O=O)
@@ -222,7 +235,7 @@ class RolloutState:
 
 
 def rollout_step(state: RolloutState, X_chunk, W1, b1, W2, b2, Q, K_chunk, V_chunk,
-                 k: int, block_len: int, act: str = "silu", forced_chunk_scores_f32=None):
+                 k: int, block_len: int, act: str = "silu", forced_chunk_scores_f32=None, n_pinned: int = 0):
     """One chunk of a rollout (Sec. 3.4 inference paragraph; Alg. 2).
 
     The chunk's scores join the stored ones after its step, so the next step's
@@ -235,7 +248,7 @@ def rollout_step(state: RolloutState, X_chunk, W1, b1, W2, b2, Q, K_chunk, V_chu
     s_chunk = smlp_score(X_chunk, W1, b1, W2, b2, act)
     s32 = (s_chunk.astype(np.float32) if forced_chunk_scores_f32 is None
            else np.asarray(forced_chunk_scores_f32, np.float32))
-    ids = select_topk(state.SL, k)
+    ids = select_topk(state.SL, k, n_pinned)
     Kk, Vk, SLk = compact_kv(state.K, state.V, state.SL, ids)
     O = chunk_attention(Q, Kk, Vk, K_chunk, V_chunk, block_len)
     state.K = np.concatenate([Kk, np.asarray(K_chunk, dtype=Kk.dtype)], axis=0)

@@ -22,7 +22,7 @@ PAFU_MODE_SINGLE, PAFU_MODE_ROLLOUT = 0, 1
 SYMBOLS = (
     "pafu_strerror", "pafu_last_hip_error", "pafu_version",
     "pafu_score_workspace_bytes", "pafu_score",
-    "pafu_select_workspace_bytes", "pafu_select_topk",
+    "pafu_select_workspace_bytes", "pafu_select_topk", "pafu_select_topk_pinned",
     "pafu_compact_kv",
     "pafu_attention_workspace_bytes", "pafu_chunk_attention",
     "pafu_step_workspace_bytes", "pafu_step", "pafu_step_layers",
@@ -51,6 +51,7 @@ class pafu_step_args(Structure):
         ("Q", c_void_p), ("K_chunk", c_void_p), ("V_chunk", c_void_p),
         ("scores", c_void_p), ("ids", c_void_p), ("K_out", c_void_p), ("V_out", c_void_p),
         ("SL_out", c_void_p), ("O", c_void_p), ("workspace", c_void_p), ("workspace_bytes", c_size_t),
+        ("n_pinned", c_int),
     ]
 
 
@@ -79,6 +80,9 @@ def _lib():
         lib.pafu_select_workspace_bytes.argtypes = [c_int]
         lib.pafu_select_topk.restype = c_int
         lib.pafu_select_topk.argtypes = [c_void_p, c_void_p, c_int, c_int, c_void_p, c_void_p, c_void_p, c_size_t]
+        lib.pafu_select_topk_pinned.restype = c_int
+        lib.pafu_select_topk_pinned.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_void_p, c_void_p, c_void_p,
+                                                c_size_t]
         lib.pafu_compact_kv.restype = c_int
         lib.pafu_compact_kv.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_longlong, c_int, c_void_p, c_int,
                                         c_int, c_int, c_int, c_void_p, c_void_p, c_void_p, c_longlong]
@@ -177,6 +181,15 @@ def pafu_select_topk(scores, k, out_ids, out_count=None, workspace=None, stream=
     return out_ids
 
 
+def pafu_select_topk_pinned(scores, k, n_pinned, out_ids, out_count=None, workspace=None, stream=None, n=None):
+    n = scores.shape[0] if n is None else n
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = _lib().pafu_select_topk_pinned(_stream(stream), _ptr(scores), n, k, n_pinned, _ptr(out_ids),
+                                        _ptr(out_count), _ptr(workspace), ws_bytes)
+    _check(rc, "pafu_select_topk_pinned")
+    return out_ids
+
+
 def pafu_compact_kv(K, V, SL, ids, count, K_out, V_out, SL_out, stream=None, n=None):
     n = K.shape[0] if n is None else n
     N, D = K.shape[1], K.shape[2]
@@ -204,7 +217,7 @@ def pafu_chunk_attention(Q, Kc, Vc, n_kept, Kn, Vn, block_len, O, softmax_scale=
 
 def make_step_args(mode, N, D, n, Lc, k, block_len, x_cache, x_chunk, W1, b1, W2, b2, K_cache, V_cache, SL_in, Q,
                    K_chunk, V_chunk, scores, ids, K_out, V_out, SL_out, O, act=PAFU_ACT_SILU, workspace=None,
-                   softmax_scale=0.0) -> pafu_step_args:
+                   softmax_scale=0.0, n_pinned=0) -> pafu_step_args:
     """Fills a pafu_step_args from torch tensors (x_cache / x_chunk: tensor or tuple of segments)."""
     a = pafu_step_args()
     xs_cache = x_cache if isinstance(x_cache, (tuple, list)) else ((x_cache,) if x_cache is not None else ())
@@ -214,6 +227,7 @@ def make_step_args(mode, N, D, n, Lc, k, block_len, x_cache, x_chunk, W1, b1, W2
     a.n_seg, a.Fs = len(xs_chunk), xs_chunk[0].shape[1]
     a.x_dtype, a.out_dtype = _dtype_code(xs_chunk[0]), _dtype_code(O)
     a.softmax_scale = float(softmax_scale)
+    a.n_pinned = int(n_pinned)
     a.ld_x = xs_chunk[0].stride(0)
     a.ld_cache = K_cache.stride(0) if K_cache is not None else N * D
     a.ld_out = K_out.stride(0)

@@ -91,7 +91,7 @@ size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 int check_step(const pafu_step_args* a) {
   if (!a) return PAFU_ERR_NULL;
   if (a->mode != PAFU_MODE_SINGLE && a->mode != PAFU_MODE_ROLLOUT) return PAFU_ERR_SHAPE;
-  if (a->n < 0 || a->k < 0 || a->Lc < 1 || a->N < 1 || a->D < 1) return PAFU_ERR_SHAPE;
+  if (a->n < 0 || a->k < 0 || a->Lc < 1 || a->N < 1 || a->D < 1 || a->n_pinned < 0) return PAFU_ERR_SHAPE;
   const int n_kept = a->k < a->n ? a->k : a->n;
   const bool single = a->mode == PAFU_MODE_SINGLE;
   if (a->workspace_bytes < pafu_step_workspace_bytes(a) || (a->workspace == nullptr && a->workspace_bytes > 0))
@@ -159,7 +159,7 @@ int enqueue_step(hipStream_t st, const pafu_step_args* a) {
   }
   const float* sel_scores = single ? a->scores : a->SL_in;
   if (a->n > 0) {
-    rc = launch_select(st, sel_scores, a->n, a->k, a->ids, nullptr, nullptr);
+    rc = launch_select(st, sel_scores, a->n, a->k, a->n_pinned, a->ids, nullptr, nullptr);
     if (rc) return rc;
     rc = launch_compact(st, a->K_cache, a->V_cache, sel_scores, a->ld_cache * 2, a->n, a->ids, n_kept,
                         a->N * a->D * 2, a->K_out, a->V_out, a->SL_out, a->ld_out * 2);
@@ -200,7 +200,7 @@ const char* pafu_strerror(int status) {
 }
 
 int pafu_last_hip_error(void) { return g_last_hip_error; }
-int pafu_version(void) { return 1; }
+int pafu_version(void) { return 2; }
 
 size_t pafu_score_workspace_bytes(int M) { return M > 0 ? ((size_t)M + 1) * sizeof(float) : 0; }
 
@@ -223,7 +223,16 @@ int pafu_select_topk(void* stream, const float* scores, int n, int k, int* out_i
   (void)workspace_bytes;
   int rc = check_select(scores, n, k, out_ids);
   if (rc) return rc;
-  return launch_select(static_cast<hipStream_t>(stream), scores, n, k, out_ids, out_count, workspace);
+  return launch_select(static_cast<hipStream_t>(stream), scores, n, k, 0, out_ids, out_count, workspace);
+}
+
+int pafu_select_topk_pinned(void* stream, const float* scores, int n, int k, int n_pinned, int* out_ids,
+                            int* out_count, void* workspace, size_t workspace_bytes) {
+  (void)workspace_bytes;
+  if (n_pinned < 0) return PAFU_ERR_SHAPE;
+  int rc = check_select(scores, n, k, out_ids);
+  if (rc) return rc;
+  return launch_select(static_cast<hipStream_t>(stream), scores, n, k, n_pinned, out_ids, out_count, workspace);
 }
 
 int pafu_compact_kv(void* stream, const void* K, const void* V, const float* SL, long long ld_in, int n, const int* ids,

@@ -28,7 +28,8 @@ int launch_compact(hipStream_t st, const void* K, const void* V, const float* SL
                    long long ld_out_bytes);
 int launch_append(hipStream_t st, const void* K, const void* V, const float* S, long long ld_in_bytes, int rows,
                   int row_bytes, void* K_out, void* V_out, float* S_out, long long ld_out_bytes);
-int launch_select(hipStream_t st, const float* scores, int n, int k, int* out_ids, int* out_count, void* ws);
+int launch_select(hipStream_t st, const float* scores, int n, int k, int n_pinned, int* out_ids, int* out_count,
+                  void* ws);
 int launch_score(hipStream_t st, const void* x0, const void* x1, const void* x2, int n_seg, int T, int Fs,
                  long long ld_x, int x_dtype, const void* W1, const float* b1, const float* W2, const float* b2,
                  int M, int n_out, int act, float* out, void* ws);

@@ -27,6 +27,7 @@ struct SelectProblem {
   int* out_count;
   int n;
   int k;
+  int n_pinned;  // tokens [0, n_pinned) rank above every score
 };
 
 // fp32 -> uint32 such that key order == (score order with -0 == +0 and NaN lowest).
@@ -35,6 +36,12 @@ __device__ __forceinline__ uint32_t score_key(float f) {
   if ((u & 0x7fffffffu) > 0x7f800000u) return 0u;  // NaN
   if (u == 0x80000000u) u = 0u;                     // -0.0 -> +0.0
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// Key of token i: the pinned prefix gets the one key no score maps to (the map's maximum is +inf = 0xff800000),
+// so pinned tokens outrank everything and, among themselves, the lower index wins like any other tie.
+__device__ __forceinline__ uint32_t token_key(float f, int i, int n_pinned) {
+  return i < n_pinned ? 0xffffffffu : score_key(f);
 }
 
 __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(SelectProblem P) {
@@ -63,7 +70,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(SelectProblem 
     for (int i = tid; i < kSelWaves * 256; i += kSelThreads) (&hist[0][0])[i] = 0u;
     __syncthreads();
     for (int i = tid; i < n; i += kSelThreads) {
-      const uint32_t key = score_key(scores[i]);
+      const uint32_t key = token_key(scores[i], i, P.n_pinned);
       const bool match = (pass == 0) || ((key >> (shift + 8)) == prefix);
       if (match) atomicAdd(&hist[wave][(key >> shift) & 255u], 1u);
     }
@@ -109,13 +116,14 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(SelectProblem 
     bool valid[4];
     if (i0 + 3 < n) {
       const float4 f = *reinterpret_cast<const float4*>(scores + i0);
-      key[0] = score_key(f.x); key[1] = score_key(f.y); key[2] = score_key(f.z); key[3] = score_key(f.w);
+      key[0] = token_key(f.x, i0, P.n_pinned); key[1] = token_key(f.y, i0 + 1, P.n_pinned);
+      key[2] = token_key(f.z, i0 + 2, P.n_pinned); key[3] = token_key(f.w, i0 + 3, P.n_pinned);
       valid[0] = valid[1] = valid[2] = valid[3] = true;
     } else {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         valid[j] = i0 + j < n;
-        key[j] = valid[j] ? score_key(scores[i0 + j]) : 0u;
+        key[j] = valid[j] ? token_key(scores[i0 + j], i0 + j, P.n_pinned) : 0u;
       }
     }
     uint32_t packed = 0;  // low 16 bits: keys > T, high 16 bits: keys == T (a tile holds 4096 keys)
@@ -217,11 +225,12 @@ __global__ __launch_bounds__(NT) void select_bitslice_kernel(SelectProblem P) {
       const int i0 = first + 32 * w + 4 * q;
       if (i0 + 3 < n) {
         const float4 f = *reinterpret_cast<const float4*>(scores + i0);
-        plane[w][4 * q + 0] = score_key(f.x); plane[w][4 * q + 1] = score_key(f.y);
-        plane[w][4 * q + 2] = score_key(f.z); plane[w][4 * q + 3] = score_key(f.w);
+        plane[w][4 * q + 0] = token_key(f.x, i0, P.n_pinned); plane[w][4 * q + 1] = token_key(f.y, i0 + 1, P.n_pinned);
+        plane[w][4 * q + 2] = token_key(f.z, i0 + 2, P.n_pinned); plane[w][4 * q + 3] = token_key(f.w, i0 + 3, P.n_pinned);
       } else {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) plane[w][4 * q + e] = i0 + e < n ? score_key(scores[i0 + e]) : 0u;
+        for (int e = 0; e < 4; ++e)
+          plane[w][4 * q + e] = i0 + e < n ? token_key(scores[i0 + e], i0 + e, P.n_pinned) : 0u;
       }
     }
     transpose32(plane[w]);
@@ -296,12 +305,13 @@ __global__ __launch_bounds__(NT) void select_bitslice_kernel(SelectProblem P) {
 
 }  // namespace
 
-int launch_select(hipStream_t st, const float* scores, int n, int k, int* out_ids, int* out_count, void* ws) {
+int launch_select(hipStream_t st, const float* scores, int n, int k, int n_pinned, int* out_ids, int* out_count,
+                  void* ws) {
   (void)ws;
   if (n <= 0 || k <= 0) {
     if (out_count == nullptr) return PAFU_OK;
   }
-  SelectProblem P{scores, out_ids, out_count, n < 0 ? 0 : n, k};
+  SelectProblem P{scores, out_ids, out_count, n < 0 ? 0 : n, k, n_pinned < 0 ? 0 : n_pinned};
   if (P.n <= 256 * 32) hipLaunchKernelGGL((select_bitslice_kernel<1, 256>), dim3(1), dim3(256), 0, st, P);
   else if (P.n <= 512 * 32 * 2) hipLaunchKernelGGL((select_bitslice_kernel<2, 512>), dim3(1), dim3(512), 0, st, P);
   else if (P.n <= 1024 * 32 * 2) hipLaunchKernelGGL((select_bitslice_kernel<2, 1024>), dim3(1), dim3(1024), 0, st, P);

@@ -92,6 +92,23 @@ def test_select_matches_oracle_with_ties(n):
             assert np.array_equal(got, orc.select_topk(s, k)), (n, k)
 
 
+@pytest.mark.parametrize("n,k,n_pinned", [(1000, 400, 100), (1000, 50, 100), (4097, 2000, 1560), (32760, 16380, 1560),
+                                         (32760, 16380, 0), (60000, 20000, 4680), (75600, 22680, 1560),
+                                         (300, 300, 10), (300, 10, 300), (64, 0, 5)])
+def test_select_pinned_prefix_matches_oracle(n, k, n_pinned):
+    rng = np.random.default_rng(n + k + n_pinned)
+    s = (rng.integers(-50, 50, size=n) * 0.25).astype(np.float32)      # many ties at the threshold
+    s[:n_pinned] -= 100.0                                              # the prefix would lose on its scores
+    s[rng.integers(0, n, 3)] = np.inf
+    m = min(k, n)
+    out = torch.full((m + 8,), -7, dtype=torch.int32, device=DEV)
+    cnt = torch.full((1,), -1, dtype=torch.int32, device=DEV)
+    B.pafu_select_topk_pinned(torch.from_numpy(s).to(DEV), k, n_pinned, out, cnt)
+    torch.cuda.synchronize()
+    assert int(cnt.item()) == m and torch.all(out[m:] == -7)
+    assert np.array_equal(out[:m].cpu().numpy(), orc.select_topk(s, k, n_pinned))
+
+
 def test_select_special_values_and_degenerate_inputs():
     s = np.array([np.nan, -np.inf, -0.0, 0.0, 1.0, np.inf, -1.0, np.nan, 0.0, -0.0, 3e-45, -3e-45], dtype=np.float32)
     for k in range(len(s) + 2):

@@ -15,7 +15,7 @@ from tests.gpu_util import ATTN_MAX_ABS, ATTN_REL_FRO, DEV, SCORE_MAX_ABS, attn_
 pytestmark = pytest.mark.gpu
 
 
-def _single(cfg, d, k, L_B, contiguous_features=True):
+def _single(cfg, d, k, L_B, contiguous_features=True, n_pinned=0):
     n, Lc, N, D = d["n"], cfg.Lc, cfg.N, cfg.D
     dt = cfg.dtype
     rb = wl.round_to_bf16
@@ -38,17 +38,17 @@ def _single(cfg, d, k, L_B, contiguous_features=True):
          dev(kv["Q"], "bf16"), dev(kv["K_chunk"], "bf16"), dev(kv["V_chunk"], "bf16")]
     args = B.make_step_args(B.PAFU_MODE_SINGLE, N, D, n, Lc, k, L_B, x_cache if n else None, x_chunk,
                             w[0], w[1], w[2], w[3], t[0], t[1], None, t[2], t[3], t[4],
-                            scores, ids, K_out, V_out, SL_out, O)
+                            scores, ids, K_out, V_out, SL_out, O, n_pinned=n_pinned)
     args._keep = (w, t, x_cache, x_chunk)
     return args, kv, scores, ids, K_out, V_out, SL_out, O, n_kept
 
 
-def _check_single(cfg, d, k, L_B, args_pack):
+def _check_single(cfg, d, k, L_B, args_pack, n_pinned=0):
     args, kv, scores, ids, K_out, V_out, SL_out, O, n_kept = args_pack
     torch.cuda.synchronize()
     got_s = host(scores)
     ref = orc.step_single(d["X_cache"], d["X_chunk"], d["W1"], d["b1"], d["W2"], d["b2"], kv["K_cache"], kv["V_cache"],
-                          kv["Q"], kv["K_chunk"], kv["V_chunk"], k, L_B, forced_scores_f32=got_s)
+                          kv["Q"], kv["K_chunk"], kv["V_chunk"], k, L_B, forced_scores_f32=got_s, n_pinned=n_pinned)
     assert np.abs(got_s - ref["scores"]).max() < SCORE_MAX_ABS
     assert np.array_equal(host(ids)[:n_kept], ref["ids"])
     assert np.array_equal(host(K_out)[:n_kept], ref["K_kept"]) and np.array_equal(host(V_out)[:n_kept], ref["V_kept"])
@@ -56,7 +56,7 @@ def _check_single(cfg, d, k, L_B, args_pack):
     max_abs, rel = attn_errors(host(O), ref["O"])
     assert max_abs < ATTN_MAX_ABS and rel < ATTN_REL_FRO, (max_abs, rel)
     # free-running check: indices may differ from the oracle's own selection only near the threshold
-    own = orc.select_topk(ref["scores"][: d["n"]].astype(np.float32), k)
+    own = orc.select_topk(ref["scores"][: d["n"]].astype(np.float32), k, n_pinned)
     diff = set(own.tolist()) ^ set(ref["ids"].tolist())
     if diff and n_kept:
         kth = np.sort(ref["scores"][: d["n"]])[::-1][n_kept - 1]
@@ -85,6 +85,20 @@ def test_step_single_c1_shaped(k_mode, L_B):
         assert np.array_equal(host(pack[4]), wl.round_to_bf16(d["K_cache"]))
 
 
+@pytest.mark.parametrize("n_pinned", [60, 270, 400])
+def test_step_single_with_frame_sink(n_pinned):
+    # the first n_pinned cached tokens (one frame = 60 tokens here) survive whatever their scores are
+    cfg = wl.scaled(wl.C1, frame_tokens=60, cache_frames=9, chunk_frames=3, k=270)     # n = 540, Lc = 180
+    d = wl.make_layer_inputs(cfg)
+    d["X_cache"][:n_pinned] -= 3.0                      # make the pinned tokens the least salient ones
+    d["X_cache"] = wl.round_to_bf16(d["X_cache"])       # keep the device cast exact
+    pack = _single(cfg, d, 270, cfg.Lc, n_pinned=n_pinned)
+    B.pafu_step(pack[0])
+    _check_single(cfg, d, 270, cfg.Lc, pack, n_pinned=n_pinned)
+    kept = host(pack[3])[:270]
+    assert kept[:min(n_pinned, 270)].tolist() == list(range(min(n_pinned, 270)))
+
+
 def test_step_single_empty_cache():
     cfg = wl.scaled(wl.C1, frame_tokens=50, cache_frames=0, chunk_frames=2, k=10)
     d = wl.make_layer_inputs(cfg)
@@ -105,7 +119,7 @@ def test_step_layers_independent():
     assert ids_seen[0] != ids_seen[1]
 
 
-def _rollout(cfg, k, n_chunks, L_B, stop_at=None, resume=None):
+def _rollout(cfg, k, n_chunks, L_B, stop_at=None, resume=None, n_pinned=0):
     """Runs the device rollout beside the oracle's (teacher-forced on the chunk scores)."""
     N, D, Lc = cfg.N, cfg.D, cfg.Lc
     W1, b1, W2, b2 = wl.make_rollout_weights(cfg, bias=True)
@@ -130,12 +144,13 @@ def _rollout(cfg, k, n_chunks, L_B, stop_at=None, resume=None):
         n_kept = min(k, n)
         args = B.make_step_args(B.PAFU_MODE_ROLLOUT, N, D, n, Lc, k, L_B, None, dev(c["X_chunk"], "bf16"), dW1, db1,
                                 dW2, db2, src["K"], src["V"], src["SL"], dev(c["Q"], "bf16"), dev(c["K_chunk"], "bf16"),
-                                dev(c["V_chunk"], "bf16"), None, ids, dst["K"], dst["V"], dst["SL"], O)
+                                dev(c["V_chunk"], "bf16"), None, ids, dst["K"], dst["V"], dst["SL"], O,
+                                n_pinned=n_pinned)
         B.pafu_step(args)
         torch.cuda.synchronize()
         s_chunk = host(dst["SL"][n_kept:n_kept + Lc])
         out = orc.rollout_step(st, c["X_chunk"], W1, b1, W2, b2, c["Q"], c["K_chunk"], c["V_chunk"], k, L_B,
-                               forced_chunk_scores_f32=s_chunk)
+                               forced_chunk_scores_f32=s_chunk, n_pinned=n_pinned)
         assert np.abs(s_chunk - out["s_chunk"]).max() < SCORE_MAX_ABS
         assert np.array_equal(host(ids)[:n_kept], out["ids"]), t
         n = n_kept + Lc
@@ -167,3 +182,14 @@ def test_rollout_full_budget_never_evicts():
     N, D, Lc = cfg.N, cfg.D, cfg.Lc
     out, sizes = _rollout(wl.scaled(cfg, k=400), 400, 5, 20)
     assert sizes == [40, 80, 120, 160, 200]
+
+
+def test_rollout_with_frame_sink_keeps_the_first_frame():
+    cfg = wl.scaled(wl.C1, frame_tokens=30, chunk_frames=3, cache_frames=0, k=240)     # Lc = 90
+    first = wl.round_to_bf16(wl.make_chunk_inputs(cfg, 0)["K_chunk"])[:30]
+    out, sizes = _rollout(cfg, 240, 8, cfg.Lc, n_pinned=30)
+    assert sizes == [90, 180, 270, 330, 330, 330, 330, 330]
+    # the first frame of the first chunk still heads the cache after five evictions
+    assert np.array_equal(host(out["K"][:30]), first)
+    plain, _ = _rollout(cfg, 240, 8, cfg.Lc)
+    assert not torch.equal(plain["K"], out["K"])

@@ -44,6 +44,8 @@ def test_select_rejects_bad_arguments():
     assert lib.pafu_select_topk(None, A, 10, -3, A, None, None, 0) == -2         # k < 0
     assert lib.pafu_select_topk(None, A + 4, 10, 3, A, None, None, 0) == -4      # misaligned
     assert lib.pafu_select_topk(None, A, 10, 3, None, None, None, 0) == -1       # NULL out
+    assert lib.pafu_select_topk_pinned(None, A, 10, 3, -1, A, None, None, 0) == -2   # n_pinned < 0
+    assert lib.pafu_select_topk_pinned(None, None, 10, 3, 2, A, None, None, 0) == -1
 
 
 def test_compact_rejects_bad_arguments():

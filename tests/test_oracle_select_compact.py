@@ -125,3 +125,68 @@ def test_compact_identity_composition_and_sync():
     # bit copy also for integer payloads (bf16 bit patterns)
     Kb = rng.integers(0, 65536, size=(n, N, D)).astype(np.uint16)
     assert np.array_equal(compact_kv(Kb, Kb, SL, a)[0], Kb[a])
+
+
+# ---------------------------------------------------------------------- pinned prefix (frame sink)
+def _brute_pinned(scores, k, n_pinned):
+    """k rounds of 'take the best remaining token'; a pinned token beats any other, pinned tokens rank by index."""
+    n = len(scores)
+    alive = list(range(n))
+    taken = []
+
+    def better(i, j):
+        pi, pj = i < n_pinned, j < n_pinned
+        if pi or pj:
+            if pi and pj:
+                return i < j
+            return pi
+        a, b = scores[i], scores[j]
+        an, bn = a != a, b != b
+        if an or bn:
+            if an and bn:
+                return i < j
+            return bn
+        if a != b:
+            return a > b
+        return i < j
+
+    for _ in range(min(k, n)):
+        best = alive[0]
+        for j in alive[1:]:
+            if better(j, best):
+                best = j
+        taken.append(best)
+        alive.remove(best)
+    return sorted(taken)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_pinned_prefix_brute_force(seed):
+    rng = np.random.default_rng(100 + seed)
+    n = int(rng.integers(2, 50))
+    s = rng.integers(-3, 4, size=n).astype(np.float32)
+    s[rng.integers(0, n)] = np.inf          # a +inf outside or inside the prefix must not change the rule
+    s[rng.integers(0, n)] = np.nan
+    for n_pinned in (0, 1, n // 3, n - 1, n, n + 3):
+        for k in (0, 1, n // 2, n - 1, n, n + 2):
+            assert select_topk(s, k, n_pinned).tolist() == _brute_pinned(s.tolist(), k, n_pinned)
+
+
+def test_pinned_prefix_invariants():
+    rng = np.random.default_rng(7)
+    n, k, p = 200, 60, 25
+    s = rng.standard_normal(n).astype(np.float32)
+    s[:p] = -10.0                                         # the prefix would all be evicted on its scores
+    ids = select_topk(s, k, p)
+    assert ids[:p].tolist() == list(range(p)) and len(ids) == k
+    # the rest is the plain top-(k - p) of the other tokens
+    assert (ids[p:] - p).tolist() == select_topk(s[p:], k - p).tolist()
+    # no prefix: the plain rule
+    assert select_topk(s, k, 0).tolist() == select_topk(s, k).tolist()
+    # same as raising the prefix above every finite score
+    t = s.copy()
+    t[:p] = np.inf
+    assert select_topk(t, k).tolist() == ids.tolist()
+    # a budget inside the prefix keeps its first k tokens; a budget covering the cache keeps everything
+    assert select_topk(s, 10, p).tolist() == list(range(10))
+    assert select_topk(s, n, p).tolist() == list(range(n))
