@@ -45,6 +45,9 @@ def parse():
     ap.add_argument("--structure", default="uniform", choices=["uniform", "coherent"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sets", type=int, default=3, help="input buffer sets rotated between steps")
+    ap.add_argument("--shared-index", action="store_true",
+                    help="C2 only: score + select once on the last layer, every layer reuses its indices (Sec. 3.3)")
+    ap.add_argument("--pinned", type=int, default=0, help="frame sink: cached tokens [0, pinned) are never evicted")
     return ap.parse_args()
 
 
@@ -78,7 +81,7 @@ def rollout(a, torch, np, B, wl):
             src, dst = slabs[cur], slabs[1 - cur]
             args = B.make_step_args(B.PAFU_MODE_ROLLOUT, N, D, n, Lc, k, Lc, None, c["X"], W1, None, W2, None, src["K"],
                                     src["V"], src["SL"], c["Q"], c["K"], c["V"], None, ids, dst["K"], dst["V"],
-                                    dst["SL"], O)
+                                    dst["SL"], O, n_pinned=a.pinned)
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
             B.pafu_step(args)
@@ -172,7 +175,8 @@ def main():
                    SL_out=torch.empty(max(n_kept, 1), device=dev), O=torch.empty(Lc, N, D, device=dev, dtype=bf))
         cur["args"] = B.make_step_args(B.PAFU_MODE_SINGLE, N, D, n, Lc, k, L_B, cur["X"][:n], cur["X"][n:], W1, b1, W2,
                                        b2, cur["K"], cur["V"], None, cur["Q"], cur["Kn"], cur["Vn"], cur["scores"],
-                                       cur["ids"], cur["K_out"], cur["V_out"], cur["SL_out"], cur["O"])
+                                       cur["ids"], cur["K_out"], cur["V_out"], cur["SL_out"], cur["O"],
+                                       n_pinned=a.pinned)
         sets.append(cur)
     torch.cuda.synchronize()
     gen_s = time.time() - t0
@@ -180,6 +184,8 @@ def main():
     def run_step(i):
         if n_layers == 1:
             B.pafu_step(sets[i % n_sets]["args"])
+        elif a.shared_index:
+            B.pafu_step_layers_shared([s["args"] for s in sets], n_layers - 1)
         else:
             B.pafu_step_layers([s["args"] for s in sets])
 
@@ -294,7 +300,9 @@ def main():
         "config": {"workload": "%s: %d layer(s), %d heads x %d, cache %d tokens, chunk %d queries, budget %d, "
                                "S-MLP %d->%d->%d, L_B=%d, salient=%s" % (a.workload, n_layers, N, D, n, Lc, k, H, M,
                                                                           cfg.n_out, L_B, a.structure),
-                   "layers": n_layers, "input_sets": n_sets},
+                   "layers": n_layers, "input_sets": n_sets,
+                   "indices": "shared (last layer's head)" if (a.shared_index and n_layers > 1) else "per layer",
+                   "n_pinned": a.pinned},
         "wall_ms_per_step": wall_ms, "stages": stages, "roofline": roofline, "cpu_baseline": cpu,
         "input_gen_s": gen_s,
     }

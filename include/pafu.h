@@ -182,6 +182,19 @@ int pafu_step(void* stream, const pafu_step_args* args /* host */);
 /* The same step for n_layers independent layers (args[l] is layer l's arguments), enqueued on one stream. */
 int pafu_step_layers(void* stream, const pafu_step_args* args /* host array */, int n_layers);
 
+/* pafu_step_layers_shared - the paper's own multi-layer arrangement (Sec. 3.3: the Salience Estimation Head sits on
+ * the final layer only and its top-k indices are applied to the caches of all layers).
+ * args[index_layer] is a complete pafu_step_args: its features, head weights and score buffers produce the scores and
+ * ONE index list (written to its `ids`).  Every layer then compacts its own K/V cache to those indices, attends, and in
+ * ROLLOUT appends its chunk rows.  For the other layers only the cache part is read (mode, n, k, Lc - which must
+ * equal the index layer's - N, D, block_len, softmax_scale, out_dtype, ld_cache/ld_out/ld_chunk/ld_o, K_cache,
+ * V_cache, Q, K_chunk, V_chunk, K_out, V_out, O); their feature, weight, score, ids and SL fields are ignored and
+ * may be NULL.  The score list is compacted and extended for the index layer only.
+ * Layers are enqueued in array order on one stream.
+ */
+int pafu_step_layers_shared(void* stream, const pafu_step_args* args /* host array */, int n_layers,
+                            int index_layer);
+
 #ifdef __cplusplus
 }
 #endif

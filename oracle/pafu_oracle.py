@@ -36,6 +36,8 @@ __all__ = [
     "step_single",
     "RolloutState",
     "rollout_step",
+    "step_single_shared",
+    "rollout_step_shared",
 ]
 
 
@@ -255,3 +257,55 @@ def rollout_step(state: RolloutState, X_chunk, W1, b1, W2, b2, Q, K_chunk, V_chu
     state.V = np.concatenate([Vk, np.asarray(V_chunk, dtype=Vk.dtype)], axis=0)
     state.SL = np.concatenate([SLk, s32]).astype(np.float32)
     return dict(s_chunk=s_chunk, ids=ids, O=O)
+
+
+# --------------------------------------------------------------------------------------
+# Final-layer head, indices shared by all layers (Sec. 3.3)
+# --------------------------------------------------------------------------------------
+def step_single_shared(X_cache, X_chunk, W1, b1, W2, b2, layers, k: int, block_len: int, act: str = "silu",
+                       forced_scores_f32=None, n_pinned: int = 0):
+    """SINGLE-mode step of several layers with ONE index list (Sec. 3.3: the head reads the final layer only and
+    its top-k indices update the caches of all layers).
+
+    X_cache / X_chunk are the index layer's features; `layers` is a list of dicts with K_cache, V_cache, Q,
+    K_chunk, V_chunk (one per layer, same token counts).
+
+    returns dict(scores f64 [n+Lc], ids, SL_kept, layers=[dict(K_kept, V_kept, O)])
+    """
+    n = X_cache.shape[0]
+    s_cache = smlp_score(X_cache, W1, b1, W2, b2, act) if n else np.zeros(0)
+    s = np.concatenate([s_cache, smlp_score(X_chunk, W1, b1, W2, b2, act)])
+    s32 = s.astype(np.float32) if forced_scores_f32 is None else np.asarray(forced_scores_f32, np.float32)
+    ids = select_topk(s32[:n], k, n_pinned)
+    outs = []
+    SLk = s32[:n][ids]
+    for L in layers:
+        assert L["K_cache"].shape[0] == n
+        Kk, Vk, _ = compact_kv(L["K_cache"], L["V_cache"], s32[:n], ids)
+        outs.append(dict(K_kept=Kk, V_kept=Vk, O=chunk_attention(L["Q"], Kk, Vk, L["K_chunk"], L["V_chunk"], block_len)))
+    return dict(scores=s, ids=ids, SL_kept=SLk, layers=outs)
+
+
+def rollout_step_shared(states, index_layer: int, X_chunk, W1, b1, W2, b2, chunks, k: int, block_len: int,
+                        act: str = "silu", forced_chunk_scores_f32=None, n_pinned: int = 0):
+    """One chunk of a multi-layer rollout with shared indices (Sec. 3.3; Alg. 2): the stored score list lives with
+    the index layer; its top-k decides which rows every layer keeps; each layer attends over its own retained rows
+    plus its own chunk rows and appends them; the chunk's scores (from the index layer's features) join the list.
+
+    states: one RolloutState per layer (only states[index_layer].SL is used); chunks: per layer dict(Q, K_chunk,
+    V_chunk).  returns dict(s_chunk f64, ids, O=[per layer]); mutates the states.
+    """
+    s_chunk = smlp_score(X_chunk, W1, b1, W2, b2, act)
+    s32 = (s_chunk.astype(np.float32) if forced_chunk_scores_f32 is None
+           else np.asarray(forced_chunk_scores_f32, np.float32))
+    SL = states[index_layer].SL
+    ids = select_topk(SL, k, n_pinned)
+    Os = []
+    for st, c in zip(states, chunks):
+        assert st.K.shape[0] == SL.shape[0]
+        Kk, Vk = st.K[ids].copy(), st.V[ids].copy()
+        Os.append(chunk_attention(c["Q"], Kk, Vk, c["K_chunk"], c["V_chunk"], block_len))
+        st.K = np.concatenate([Kk, np.asarray(c["K_chunk"], dtype=Kk.dtype)], axis=0)
+        st.V = np.concatenate([Vk, np.asarray(c["V_chunk"], dtype=Vk.dtype)], axis=0)
+    states[index_layer].SL = np.concatenate([SL[ids], s32]).astype(np.float32)
+    return dict(s_chunk=s_chunk, ids=ids, O=Os)

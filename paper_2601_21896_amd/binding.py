@@ -25,7 +25,7 @@ SYMBOLS = (
     "pafu_select_workspace_bytes", "pafu_select_topk", "pafu_select_topk_pinned",
     "pafu_compact_kv",
     "pafu_attention_workspace_bytes", "pafu_chunk_attention",
-    "pafu_step_workspace_bytes", "pafu_step", "pafu_step_layers",
+    "pafu_step_workspace_bytes", "pafu_step", "pafu_step_layers", "pafu_step_layers_shared",
 )
 
 
@@ -98,6 +98,8 @@ def _lib():
         lib.pafu_step.argtypes = [c_void_p, POINTER(pafu_step_args)]
         lib.pafu_step_layers.restype = c_int
         lib.pafu_step_layers.argtypes = [c_void_p, POINTER(pafu_step_args), c_int]
+        lib.pafu_step_layers_shared.restype = c_int
+        lib.pafu_step_layers_shared.argtypes = [c_void_p, POINTER(pafu_step_args), c_int, c_int]
         _LIB = lib
     return _LIB
 
@@ -260,3 +262,9 @@ def pafu_step(args: pafu_step_args, stream=None):
 def pafu_step_layers(args_list, stream=None):
     arr = (pafu_step_args * len(args_list))(*args_list)
     _check(_lib().pafu_step_layers(_stream(stream), arr, len(args_list)), "pafu_step_layers")
+
+
+def pafu_step_layers_shared(args_list, index_layer, stream=None):
+    arr = (pafu_step_args * len(args_list))(*args_list)
+    _check(_lib().pafu_step_layers_shared(_stream(stream), arr, len(args_list), index_layer),
+           "pafu_step_layers_shared")

@@ -126,10 +126,11 @@ int check_step(const pafu_step_args* a) {
   return PAFU_OK;
 }
 
-int enqueue_step(hipStream_t st, const pafu_step_args* a) {
+// The scoring part of a step: SINGLE scores cache + chunk into a->scores, ROLLOUT the chunk into SL_out behind the
+// retained rows.
+int enqueue_scores(hipStream_t st, const pafu_step_args* a) {
   const int n_kept = a->k < a->n ? a->k : a->n;
   const bool single = a->mode == PAFU_MODE_SINGLE;
-  const float scale = a->softmax_scale > 0.f ? a->softmax_scale : 1.0f / sqrtf((float)a->D);
   int rc;
   float* chunk_scores = single ? a->scores + a->n : a->SL_out + n_kept;
   if (single && a->n > 0) {
@@ -157,23 +158,60 @@ int enqueue_step(hipStream_t st, const pafu_step_args* a) {
                       a->W1, a->b1, a->W2, a->b2, a->M, a->n_out, a->act, chunk_scores, a->workspace);
     if (rc) return rc;
   }
-  const float* sel_scores = single ? a->scores : a->SL_in;
+  return PAFU_OK;
+}
+
+// The cache part of a step for one layer: compact K/V (and the score list when sel_scores is given) to `ids`,
+// attend over retained + chunk, and in ROLLOUT append the chunk's K/V behind the retained rows.
+int enqueue_kv(hipStream_t st, const pafu_step_args* a, const int* ids, const float* sel_scores, float* SL_out) {
+  const int n_kept = a->k < a->n ? a->k : a->n;
+  const float scale = a->softmax_scale > 0.f ? a->softmax_scale : 1.0f / sqrtf((float)a->D);
+  int rc;
   if (a->n > 0) {
-    rc = launch_select(st, sel_scores, a->n, a->k, a->n_pinned, a->ids, nullptr, nullptr);
-    if (rc) return rc;
-    rc = launch_compact(st, a->K_cache, a->V_cache, sel_scores, a->ld_cache * 2, a->n, a->ids, n_kept,
-                        a->N * a->D * 2, a->K_out, a->V_out, a->SL_out, a->ld_out * 2);
+    rc = launch_compact(st, a->K_cache, a->V_cache, sel_scores, a->ld_cache * 2, a->n, ids, n_kept, a->N * a->D * 2,
+                        a->K_out, a->V_out, SL_out, a->ld_out * 2);
     if (rc) return rc;
   }
   rc = launch_attention(st, a->Q, a->Lc, a->K_out, a->V_out, n_kept, a->K_chunk, a->V_chunk, a->Lc, a->N, a->D,
                         a->ld_chunk, a->ld_out, a->ld_chunk, a->ld_o, a->block_len, scale, a->O, a->out_dtype);
   if (rc) return rc;
-  if (!single) {
+  if (a->mode != PAFU_MODE_SINGLE) {
     char* ko = static_cast<char*>(a->K_out) + (long long)n_kept * a->ld_out * 2;
     char* vo = static_cast<char*>(a->V_out) + (long long)n_kept * a->ld_out * 2;
     rc = launch_append(st, a->K_chunk, a->V_chunk, nullptr, a->ld_chunk * 2, a->Lc, a->N * a->D * 2, ko, vo, nullptr,
                        a->ld_out * 2);
     if (rc) return rc;
+  }
+  return PAFU_OK;
+}
+
+int enqueue_step(hipStream_t st, const pafu_step_args* a) {
+  int rc = enqueue_scores(st, a);
+  if (rc) return rc;
+  const float* sel_scores = a->mode == PAFU_MODE_SINGLE ? a->scores : a->SL_in;
+  if (a->n > 0) {
+    rc = launch_select(st, sel_scores, a->n, a->k, a->n_pinned, a->ids, nullptr, nullptr);
+    if (rc) return rc;
+  }
+  return enqueue_kv(st, a, a->ids, sel_scores, a->SL_out);
+}
+
+// Validates the cache part of a layer that takes its indices from another layer.
+int check_layer_kv(const pafu_step_args* a, const pafu_step_args* idx) {
+  if (!a) return PAFU_ERR_NULL;
+  if (a->mode != idx->mode || a->n != idx->n || a->k != idx->k || a->Lc != idx->Lc) return PAFU_ERR_SHAPE;
+  if (a->N < 1 || a->D < 1) return PAFU_ERR_SHAPE;
+  const int n_kept = a->k < a->n ? a->k : a->n;
+  int rc = check_compact(a->K_cache, a->V_cache, nullptr, a->ld_cache, a->n, idx->ids, n_kept, a->N, a->D, PAFU_BF16,
+                         a->K_out, a->V_out, nullptr, a->ld_out);
+  if (rc) return rc;
+  rc = check_attention(a->Q, a->Lc, a->K_out, a->V_out, n_kept, a->K_chunk, a->V_chunk, a->Lc, a->N, a->D, a->ld_chunk,
+                       a->ld_out, a->ld_chunk, a->ld_o, a->block_len, a->O, a->out_dtype);
+  if (rc) return rc;
+  if (a->mode != PAFU_MODE_SINGLE) {
+    if (!a->K_out || !a->V_out) return PAFU_ERR_NULL;
+    if (!aligned16(a->K_out) || !aligned16(a->V_out) || (a->ld_out * 2) % 16 != 0) return PAFU_ERR_ALIGN;
+    if (a->ld_out < (long long)a->N * a->D) return PAFU_ERR_SHAPE;
   }
   return PAFU_OK;
 }
@@ -281,6 +319,35 @@ int pafu_step_layers(void* stream, const pafu_step_args* args, int n_layers) {
   }
   for (int l = 0; l < n_layers; ++l) {
     int rc = enqueue_step(static_cast<hipStream_t>(stream), &args[l]);
+    if (rc) return rc;
+  }
+  return PAFU_OK;
+}
+
+int pafu_step_layers_shared(void* stream, const pafu_step_args* args, int n_layers, int index_layer) {
+  if (n_layers < 1 || index_layer < 0 || index_layer >= n_layers) return PAFU_ERR_SHAPE;
+  if (!args) return PAFU_ERR_NULL;
+  const pafu_step_args* idx = &args[index_layer];
+  int rc = check_step(idx);
+  if (rc) return rc;
+  for (int l = 0; l < n_layers; ++l) {  // validate every layer before enqueuing anything
+    if (l == index_layer) continue;
+    rc = check_layer_kv(&args[l], idx);
+    if (rc) return rc;
+  }
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  // ROLLOUT selects on the stored list, so the indices exist before any layer runs; the chunk's own scores are only
+  // needed for the append.  SINGLE scores first.  Either way: scores, one selection, then every layer's cache.
+  rc = enqueue_scores(st, idx);
+  if (rc) return rc;
+  const float* sel_scores = idx->mode == PAFU_MODE_SINGLE ? idx->scores : idx->SL_in;
+  if (idx->n > 0) {
+    rc = launch_select(st, sel_scores, idx->n, idx->k, idx->n_pinned, idx->ids, nullptr, nullptr);
+    if (rc) return rc;
+  }
+  for (int l = 0; l < n_layers; ++l) {
+    const bool is_idx = l == index_layer;
+    rc = enqueue_kv(st, &args[l], idx->ids, is_idx ? sel_scores : nullptr, is_idx ? idx->SL_out : nullptr);
     if (rc) return rc;
   }
   return PAFU_OK;

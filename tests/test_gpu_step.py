@@ -193,3 +193,77 @@ def test_rollout_with_frame_sink_keeps_the_first_frame():
     assert np.array_equal(host(out["K"][:30]), first)
     plain, _ = _rollout(cfg, 240, 8, cfg.Lc)
     assert not torch.equal(plain["K"], out["K"])
+
+
+# ------------------------------------------------------------------ shared indices across layers (Sec. 3.3)
+@pytest.mark.parametrize("n_pinned", [0, 40])
+def test_step_layers_shared_single(n_pinned):
+    cfg = wl.scaled(wl.C1, frame_tokens=40, cache_frames=6, chunk_frames=2, k=120)      # n = 240, Lc = 80
+    layers = [wl.make_layer_inputs(cfg, seed=wl.BASE_SEED + 7 + 1000 * l) for l in range(3)]
+    idx = 2
+    packs = [_single(cfg, d, cfg.k, cfg.Lc, n_pinned=n_pinned) for d in layers]
+    for p in packs[:idx]:
+        p[3].fill_(-5)                                       # ids of the other layers must stay untouched
+    B.pafu_step_layers_shared([p[0] for p in packs], idx)
+    torch.cuda.synchronize()
+    d = layers[idx]
+    got_s = host(packs[idx][2])
+    kvs = [p[1] for p in packs]
+    ref = orc.step_single_shared(d["X_cache"], d["X_chunk"], d["W1"], d["b1"], d["W2"], d["b2"], kvs, cfg.k, cfg.Lc,
+                                 forced_scores_f32=got_s, n_pinned=n_pinned)
+    assert np.abs(got_s - ref["scores"]).max() < SCORE_MAX_ABS
+    n_kept = cfg.k
+    assert np.array_equal(host(packs[idx][3])[:n_kept], ref["ids"])
+    assert np.array_equal(host(packs[idx][6])[:n_kept], ref["SL_kept"])
+    for l, (p, out) in enumerate(zip(packs, ref["layers"])):
+        assert np.array_equal(host(p[4])[:n_kept], out["K_kept"]) and np.array_equal(host(p[5])[:n_kept], out["V_kept"]), l
+        max_abs, rel = attn_errors(host(p[7]), out["O"])
+        assert max_abs < ATTN_MAX_ABS and rel < ATTN_REL_FRO, (l, max_abs, rel)
+    for p in packs[:idx]:
+        assert torch.all(p[3] == -5)
+    # the layers do differ: same rows kept, different contents
+    assert not np.array_equal(host(packs[0][4]), host(packs[1][4]))
+
+
+def test_step_layers_shared_rollout():
+    cfg = wl.scaled(wl.C1, frame_tokens=30, chunk_frames=2, cache_frames=0, k=150)      # Lc = 60
+    N, D, Lc, k, n_layers, idx = cfg.N, cfg.D, cfg.Lc, 150, 3, 2
+    W1, b1, W2, b2 = wl.make_rollout_weights(cfg, bias=True)
+    dW = (dev(W1, "bf16"), dev(b1), dev(W2), dev(b2))
+    cap = k + Lc
+    slabs = [[dict(K=torch.zeros(cap, N, D, device=DEV, dtype=torch.bfloat16),
+                   V=torch.zeros(cap, N, D, device=DEV, dtype=torch.bfloat16),
+                   SL=torch.zeros(cap, device=DEV)) for _ in range(2)] for _ in range(n_layers)]
+    states = [orc.RolloutState(N, D, np.float32) for _ in range(n_layers)]
+    ids = torch.empty(k, dtype=torch.int32, device=DEV)
+    Os = [torch.empty(Lc, N, D, device=DEV, dtype=torch.bfloat16) for _ in range(n_layers)]
+    n, cur = 0, 0
+    for t in range(6):
+        chunks = [wl.make_chunk_inputs(cfg, 10 * t + l) for l in range(n_layers)]
+        X = chunks[idx]["X_chunk"]
+        n_kept = min(k, n)
+        args = []
+        for l in range(n_layers):
+            src, dst, c = slabs[l][cur], slabs[l][1 - cur], chunks[l]
+            is_idx = l == idx
+            args.append(B.make_step_args(
+                B.PAFU_MODE_ROLLOUT, N, D, n, Lc, k, Lc, None, dev(X, "bf16"), dW[0], dW[1], dW[2], dW[3],
+                src["K"], src["V"], src["SL"] if is_idx else None, dev(c["Q"], "bf16"), dev(c["K_chunk"], "bf16"),
+                dev(c["V_chunk"], "bf16"), None, ids if is_idx else None, dst["K"], dst["V"],
+                dst["SL"] if is_idx else None, Os[l], n_pinned=30))
+        B.pafu_step_layers_shared(args, idx)
+        torch.cuda.synchronize()
+        s_chunk = host(slabs[idx][1 - cur]["SL"][n_kept:n_kept + Lc])
+        out = orc.rollout_step_shared(states, idx, X, W1, b1, W2, b2, chunks, k, Lc, forced_chunk_scores_f32=s_chunk,
+                                      n_pinned=30)
+        assert np.abs(s_chunk - out["s_chunk"]).max() < SCORE_MAX_ABS
+        assert np.array_equal(host(ids)[:n_kept], out["ids"]), t
+        n = n_kept + Lc
+        for l in range(n_layers):
+            dst = slabs[l][1 - cur]
+            assert np.array_equal(host(dst["K"][:n]), states[l].K) and np.array_equal(host(dst["V"][:n]), states[l].V), (t, l)
+            max_abs, rel = attn_errors(host(Os[l]), out["O"][l])
+            assert max_abs < ATTN_MAX_ABS and rel < ATTN_REL_FRO, (t, l, max_abs, rel)
+        assert np.array_equal(host(slabs[idx][1 - cur]["SL"][:n]), states[idx].SL), t
+        cur = 1 - cur
+    assert n == k + Lc

@@ -121,3 +121,11 @@ def test_step_rejects_bad_arguments():
     assert lib.pafu_step(None, ctypes.byref(a)) == -2
     assert lib.pafu_step_layers(None, None, 2) == -1
     assert lib.pafu_step_layers(None, None, 0) == 0
+    assert lib.pafu_step_layers_shared(None, None, 2, 0) == -1
+    assert lib.pafu_step_layers_shared(None, ctypes.byref(a), 0, 0) == -2        # no layers
+    assert lib.pafu_step_layers_shared(None, ctypes.byref(a), 1, 1) == -2        # index layer out of range
+    assert lib.pafu_step_layers_shared(None, ctypes.byref(a), 1, 0) == -2        # the index layer is validated in full
+    a.mode = 0
+    a.n_pinned = -1
+    a.Lc = a.N = a.D = 1
+    assert lib.pafu_step(None, ctypes.byref(a)) == -2                             # negative frame sink

@@ -224,3 +224,51 @@ def test_rollout_sizes_competition_and_resume():
     # stored scores are never refreshed: every stored score is one some chunk produced
     produced = np.concatenate([smlp_score(c["X_chunk"], W1, None, W2, None).astype(np.float32) for c in chunks])
     assert set(st.SL.tolist()) <= set(produced.tolist())
+
+
+# ---------------------------------------------------------------------- shared indices across layers (Sec. 3.3)
+def test_shared_step_uses_one_index_list_for_every_layer():
+    from oracle.pafu_oracle import step_single_shared
+    rng = np.random.default_rng(21)
+    n, Lc, N, D, k = 24, 6, 2, 4, 9
+    inp = _step_inputs(rng, n, Lc, N, D, 6)
+    kv_keys = ("K_cache", "V_cache", "Q", "K_chunk", "V_chunk")
+    layers = [{key: rng.standard_normal(inp[key].shape) for key in kv_keys} for _ in range(2)]
+    layers.append({key: inp[key] for key in kv_keys})          # the index layer's own cache goes last
+    head = {key: inp[key] for key in ("X_cache", "X_chunk", "W1", "b1", "W2", "b2")}
+    r = step_single_shared(**head, layers=layers, k=k, block_len=3)
+    own = step_single(**inp, k=k, block_len=3)
+    # the index layer behaves exactly like an independent step ...
+    assert np.array_equal(r["ids"], own["ids"]) and np.array_equal(r["scores"], own["scores"])
+    assert np.array_equal(r["layers"][2]["O"], own["O"]) and np.array_equal(r["layers"][2]["K_kept"], own["K_kept"])
+    assert np.array_equal(r["SL_kept"], own["SL_kept"])
+    # ... and every other layer keeps the SAME rows of its own cache, attends over them row by row as written
+    for L, out in zip(layers[:2], r["layers"][:2]):
+        for row, i in enumerate(r["ids"]):
+            assert np.array_equal(out["K_kept"][row], L["K_cache"][i]) and np.array_equal(out["V_kept"][row], L["V_cache"][i])
+        loops = _loops(L["Q"], L["K_cache"][r["ids"]], L["V_cache"][r["ids"]], L["K_chunk"], L["V_chunk"], 3)
+        assert np.allclose(out["O"], loops, rtol=1e-12, atol=1e-13)
+    # with a frame sink the first tokens stay in every layer
+    r2 = step_single_shared(**head, layers=layers, k=k, block_len=3, n_pinned=4)
+    assert r2["ids"][:4].tolist() == [0, 1, 2, 3]
+
+
+def test_shared_rollout_keeps_layers_in_lockstep():
+    from oracle.pafu_oracle import rollout_step_shared
+    rng = np.random.default_rng(22)
+    N, D, Lc, k, M, n_layers = 2, 4, 5, 8, 5, 3
+    H = N * D
+    W1 = rng.standard_normal((M, H)) * 0.3
+    W2 = rng.standard_normal((1, M))
+    states = [RolloutState(N, D, np.float64) for _ in range(n_layers)]
+    solo = RolloutState(N, D, np.float64)                      # the index layer run on its own
+    for t in range(5):
+        X = rng.standard_normal((Lc, H))
+        chunks = [dict(Q=rng.standard_normal((Lc, N, D)), K_chunk=rng.standard_normal((Lc, N, D)),
+                       V_chunk=rng.standard_normal((Lc, N, D))) for _ in range(n_layers)]
+        out = rollout_step_shared(states, n_layers - 1, X, W1, None, W2, None, chunks, k, Lc)
+        ref = rollout_step(solo, X, W1, None, W2, None, chunks[-1]["Q"], chunks[-1]["K_chunk"], chunks[-1]["V_chunk"], k, Lc)
+        assert np.array_equal(out["ids"], ref["ids"]) and np.array_equal(out["O"][-1], ref["O"])
+        assert np.array_equal(states[-1].K, solo.K) and np.array_equal(states[-1].SL, solo.SL)
+        assert len({st.n for st in states}) == 1                # all layers hold the same number of rows
+    assert states[0].n == min(k, 4 * Lc) + Lc
