@@ -132,6 +132,20 @@ int pafu_chunk_attention(void* stream, const void* Q, int Lq, const void* Kc, co
                          float softmax_scale, void* O, int out_dtype, void* workspace,
                          size_t workspace_bytes);
 
+/* pafu_chunk_attention_gather - the same attention with index-based Select (Sec. 3.4; Eq. 7): the cache stays
+ * uncompacted and the retained rows are read through an index list, so no compaction pass precedes the call.
+ *   K_cache, V_cache : [n_cache, N, D] bf16, stride ld_c      ids : [n_kept] int32 (device, 16-byte aligned)
+ * Retained row r is cache row ids[r]; O equals pafu_chunk_attention on the cache compacted to ids (the order of
+ * ids does not matter to the result beyond summation order).  An id outside [0, n_cache) is clamped into the range
+ * (no access leaves the cache; the output is then meaningless).  n_kept <= n_cache, and a cache tensor must span
+ * less than 4 GiB (n_cache * ld_c * 2 bytes).  Everything else as above.
+ */
+int pafu_chunk_attention_gather(void* stream, const void* Q, int Lq, const void* K_cache, const void* V_cache,
+                                int n_cache, const int* ids, int n_kept, const void* Kn, const void* Vn, int Lc,
+                                int N, int D, long long ld_q, long long ld_c, long long ld_n, long long ld_o,
+                                int block_len, float softmax_scale, void* O, int out_dtype, void* workspace,
+                                size_t workspace_bytes);
+
 /* ------------------------------------------------------------------------------------------
  * pafu_step - one chunk step of one layer on one stream, Alg. 2; Sec. 3.4.
  *

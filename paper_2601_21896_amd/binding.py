@@ -24,7 +24,7 @@ SYMBOLS = (
     "pafu_score_workspace_bytes", "pafu_score",
     "pafu_select_workspace_bytes", "pafu_select_topk", "pafu_select_topk_pinned",
     "pafu_compact_kv",
-    "pafu_attention_workspace_bytes", "pafu_chunk_attention",
+    "pafu_attention_workspace_bytes", "pafu_chunk_attention", "pafu_chunk_attention_gather",
     "pafu_step_workspace_bytes", "pafu_step", "pafu_step_layers", "pafu_step_layers_shared",
 )
 
@@ -92,6 +92,11 @@ def _lib():
         lib.pafu_chunk_attention.argtypes = [c_void_p, c_void_p, c_int, c_void_p, c_void_p, c_int, c_void_p, c_void_p,
                                              c_int, c_int, c_int, c_longlong, c_longlong, c_longlong, c_longlong,
                                              c_int, c_float, c_void_p, c_int, c_void_p, c_size_t]
+        lib.pafu_chunk_attention_gather.restype = c_int
+        lib.pafu_chunk_attention_gather.argtypes = [c_void_p, c_void_p, c_int, c_void_p, c_void_p, c_int, c_void_p,
+                                                    c_int, c_void_p, c_void_p, c_int, c_int, c_int, c_longlong,
+                                                    c_longlong, c_longlong, c_longlong, c_int, c_float, c_void_p,
+                                                    c_int, c_void_p, c_size_t]
         lib.pafu_step_workspace_bytes.restype = c_size_t
         lib.pafu_step_workspace_bytes.argtypes = [POINTER(pafu_step_args)]
         lib.pafu_step.restype = c_int
@@ -214,6 +219,19 @@ def pafu_chunk_attention(Q, Kc, Vc, n_kept, Kn, Vn, block_len, O, softmax_scale=
                                      Lc, N, D, Q.stride(0), ld_c, Kn.stride(0), O.stride(0), block_len,
                                      float(softmax_scale), _ptr(O), _dtype_code(O), _ptr(workspace), ws_bytes)
     _check(rc, "pafu_chunk_attention")
+    return O
+
+
+def pafu_chunk_attention_gather(Q, K_cache, V_cache, ids, n_kept, Kn, Vn, block_len, O, softmax_scale=0.0,
+                                workspace=None, stream=None):
+    Lq, N, D = Q.shape
+    Lc = Kn.shape[0]
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = _lib().pafu_chunk_attention_gather(_stream(stream), _ptr(Q), Lq, _ptr(K_cache), _ptr(V_cache),
+                                            K_cache.shape[0], _ptr(ids), n_kept, _ptr(Kn), _ptr(Vn), Lc, N, D,
+                                            Q.stride(0), K_cache.stride(0), Kn.stride(0), O.stride(0), block_len,
+                                            float(softmax_scale), _ptr(O), _dtype_code(O), _ptr(workspace), ws_bytes)
+    _check(rc, "pafu_chunk_attention_gather")
     return O
 
 

@@ -299,6 +299,27 @@ int pafu_chunk_attention(void* stream, const void* Q, int Lq, const void* Kc, co
                           ld_o, block_len, scale, O, out_dtype);
 }
 
+int pafu_chunk_attention_gather(void* stream, const void* Q, int Lq, const void* K_cache, const void* V_cache,
+                                int n_cache, const int* ids, int n_kept, const void* Kn, const void* Vn, int Lc, int N,
+                                int D, long long ld_q, long long ld_c, long long ld_n, long long ld_o, int block_len,
+                                float softmax_scale, void* O, int out_dtype, void* workspace,
+                                size_t workspace_bytes) {
+  (void)workspace; (void)workspace_bytes;
+  if (n_cache < 0 || n_kept < 0 || n_kept > n_cache) return PAFU_ERR_SHAPE;
+  if (n_kept > 0 && !ids) return PAFU_ERR_NULL;
+  if (!aligned16(ids)) return PAFU_ERR_ALIGN;
+  // the kernel addresses gathered rows by 32-bit byte offsets from the head's base
+  if ((long long)n_cache * ld_c * 2 >= (1ll << 32)) return PAFU_ERR_SHAPE;
+  // the retained rows are a subset of the cache: validate the cache extent (alias check included) with the
+  // checker of the plain call
+  int rc = check_attention(Q, Lq, K_cache, V_cache, n_cache, Kn, Vn, Lc, N, D, ld_q, ld_c, ld_n, ld_o, block_len, O,
+                           out_dtype);
+  if (rc) return rc;
+  const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)D);
+  return launch_attention(static_cast<hipStream_t>(stream), Q, Lq, K_cache, V_cache, n_kept, Kn, Vn, Lc, N, D, ld_q,
+                          ld_c, ld_n, ld_o, block_len, scale, O, out_dtype, ids, n_cache);
+}
+
 size_t pafu_step_workspace_bytes(const pafu_step_args* a) {
   if (!a) return 0;
   return a->n_out > 1 ? align_up(pafu_score_workspace_bytes(a->M)) : 0;

@@ -57,6 +57,8 @@ struct AttnParams {
   const unsigned short* Kn;
   const unsigned short* Vn;
   void* O;
+  const int* ids;  // gather variant: retained row r of the cache segment is row ids[r] of Kc / Vc
+  int n_cache;     // rows behind Kc / Vc in the gather variant
   long long ld_q, ld_c, ld_n, ld_o;
   int Lq, n_kept, Lc, block_len;
   float scale_log2;  // softmax scale * log2(e)
@@ -67,9 +69,15 @@ constexpr int kAtThreads = kAtWaves * 64;
 constexpr int kAtBQ = kAtWaves * 32;  // queries per workgroup
 constexpr int kAtTileKeys = 64;       // keys per LDS tile = keys per pipeline step
 constexpr int kAtStages = 4;          // LDS ring depth (tiles)
+constexpr int kAtIdStages = 8;        // ids ring depth (gather variant): a tile's ids live from 3 steps before its
+                                      // K load to its V load two steps after that
+constexpr int kAtIdLead = 3;
+constexpr int kAtXcds = 8;            // accelerator dies, each with its own L2
 constexpr float kAtLazyLog2 = 8.0f;   // raise the running maximum only when it grows by more than 2^8
 
-constexpr int attn_lds_bytes(int D) { return 2 * kAtStages * kAtTileKeys * 2 * D; }
+constexpr int attn_lds_bytes(int D, bool gather = false) {
+  return 2 * kAtStages * kAtTileKeys * 2 * D + (gather ? kAtIdStages * kAtTileKeys * 4 : 0);
+}
 
 typedef __attribute__((address_space(3))) unsigned char lds_byte;
 
@@ -89,6 +97,14 @@ __device__ __forceinline__ void dma_row_chunks(const void* src, unsigned lds_add
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
                :
                : "s"(lds_addr_uniform), "v"(src)
+               : "memory");
+}
+
+// The same copy addressed as a wave-uniform base plus a 32-bit per-lane byte offset.
+__device__ __forceinline__ void dma_row_chunks_at(const void* base_uniform, unsigned byte_off, unsigned lds_addr_uniform) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(lds_addr_uniform), "v"(byte_off), "s"(base_uniform)
                : "memory");
 }
 
@@ -224,7 +240,12 @@ __device__ __forceinline__ void attn_mask(f32x16 (&s)[2], int key0, int lim, int
     }
 }
 
-template <int D, bool OUT_F32>
+// GATHER: the cache segment is read through an index list (index-based Select, Sec. 3.4; Eq. 7): K/V stay
+// uncompacted and tile row r comes from cache row ids[r].  The 64 ids of a tile travel global -> LDS like the tiles
+// themselves (one 4-byte-per-lane load per wave and step, three steps ahead of the K tile that needs them, into a
+// small ring of their own), so the vector-memory queue stays one hand-counted stream and a lane picks up its row
+// index with one LDS read.
+template <int D, bool OUT_F32, bool GATHER>
 __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnParams p) {
   constexpr int ROWB = 2 * D;                  // bytes per K/V row of one head
   constexpr int TILEB = kAtTileKeys * ROWB;    // bytes per K (or V) tile
@@ -240,8 +261,15 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnPara
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 5, c = lane & 31;
-  const int h = blockIdx.y;
-  const int i_first = blockIdx.x * kAtBQ;
+  // Workgroup -> (head, query tile).  Workgroups are handed to the 8 XCDs round-robin in launch order and every XCD
+  // has its own L2, so XCD x (workgroups x, x + 8, ...) takes one contiguous range of the head-major work list:
+  // at any time an XCD then streams the K/V of one or two heads instead of all of them.
+  const int n_qt = (p.Lq + kAtBQ - 1) / kAtBQ;
+  const int total = gridDim.x;
+  const int xcd = blockIdx.x % kAtXcds, slot = blockIdx.x / kAtXcds;
+  const int work = xcd * (total / kAtXcds) + (xcd < total % kAtXcds ? xcd : total % kAtXcds) + slot;
+  const int h = work / n_qt;
+  const int i_first = (work - h * n_qt) * kAtBQ;
   const int i_last = (i_first + kAtBQ - 1 < p.Lq) ? i_first + kAtBQ - 1 : p.Lq - 1;
   const int L_B = p.block_len;
   const int n_total = p.n_kept + p.Lc;
@@ -277,6 +305,23 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnPara
     v_offc[j] = (unsigned)(row * ldc_b) + vch * 16;
     v_offn[j] = (unsigned)(row * ldn_b) + vch * 16;
   }
+  // ids ring (gather variant): slot u % kAtIdStages holds the 64 ids of tile u, clamped to the list's end
+  int* const id_ring = reinterpret_cast<int*>(lds_raw + 2 * kAtStages * TILEB);
+  auto issue_ids = [&](int tile) {
+    if (lane < 8) {  // wave w brings ids 8 w .. 8 w + 7 of the tile: one load per wave, 64 ids per workgroup
+      int idx = tile * kAtTileKeys + 8 * wave + lane;
+      idx = idx < p.n_kept ? idx : p.n_kept - 1;
+      lds_byte* dst = (lds_byte*)(id_ring + (tile % kAtIdStages) * kAtTileKeys + 8 * wave);
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+                   :
+                   : "s"(__builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)dst)), "v"((unsigned)idx * 4u), "s"(p.ids)
+                   : "memory");
+    }
+  };
+  auto tile_id = [&](int tile, int row) {  // cache row behind tile row `row`, never outside the cache
+    const int id = ((const __attribute__((address_space(3))) int*)id_ring)[(tile % kAtIdStages) * kAtTileKeys + row];
+    return id < 0 ? 0 : (id < p.n_cache ? id : p.n_cache - 1);
+  };
   auto issue_one = [&](int tile, const unsigned short* cache, const unsigned short* chunk, lds_byte* ring,
                        const unsigned (&offc)[LPT], const unsigned (&offn)[LPT], bool is_v) {
     const int stage = tile % kAtStages;
@@ -285,12 +330,28 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnPara
     const char* base_n = reinterpret_cast<const char*>(chunk + head_off) - (long long)p.n_kept * ldn_b;
     const bool all_cache = key0 + kAtTileKeys <= p.n_kept;
     const bool all_chunk = key0 >= p.n_kept && key0 + kAtTileKeys <= n_total;
-    if (all_cache || all_chunk) {  // workgroup-uniform
+    if (GATHER && all_cache) {  // workgroup-uniform
+      // Registers are scarce here, so nothing per-lane is kept between steps: the swizzled chunk is recomputed (it
+      // does not depend on j: consecutive loads of a wave are 8 RPI rows apart) and the address is the head's
+      // base plus a 32-bit offset (the host rejects caches of 4 GiB or more per tensor for this variant).
+      const int rl = lane / CH, slot = lane % CH;
+      const int row0 = wave * RPI + rl;  // the tile row of load 0
+      const unsigned chunk16 =
+          (unsigned)((is_v ? slot ^ (4 * ((row0 / RPB) & (CH / 4 - 1))) : slot ^ ((row0 / RPB) & (CH - 1))) << 4);
+#pragma unroll
+      for (int j = 0; j < LPT; ++j) {
+        const int id = tile_id(tile, (wave + kAtWaves * j) * RPI + rl);
+        lds_byte* dst = ring + stage * TILEB + (wave + kAtWaves * j) * 1024;
+        dma_row_chunks_at(base_c, (unsigned)id * (unsigned)ldc_b + chunk16,
+                          __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)dst));
+      }
+    } else if (all_cache || all_chunk) {  // workgroup-uniform
       const char* tile_base = all_cache ? base_c + (long long)key0 * ldc_b : base_n + (long long)key0 * ldn_b;
 #pragma unroll
       for (int j = 0; j < LPT; ++j) {
         lds_byte* dst = ring + stage * TILEB + (wave + kAtWaves * j) * 1024;
-        dma_row_chunks(tile_base + (all_cache ? offc[j] : offn[j]), __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)dst));
+        const unsigned off = GATHER ? offn[0] + (unsigned)(j * kAtWaves * RPI * ldn_b) : (all_cache ? offc[j] : offn[j]);
+        dma_row_chunks(tile_base + off, __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)dst));
       }
     } else {
 #pragma unroll
@@ -301,6 +362,7 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnPara
         int kidx = key0 + row;
         kidx = kidx < n_total ? kidx : n_total - 1;
         const bool in_cache = kidx < p.n_kept;
+        if (GATHER && in_cache) kidx = tile_id(tile, row);
         const char* src = (in_cache ? base_c : base_n) +
                           (unsigned long long)(unsigned)kidx * (unsigned long long)(in_cache ? ldc_b : ldn_b) + ch * 16;
         lds_byte* dst = ring + stage * TILEB + (wave + kAtWaves * j) * 1024;
@@ -310,6 +372,7 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnPara
   };
   // Step t reads K tile t+1 and V tile t-1.  At its start K(t+S) and V(t+S-2) are issued into the slots of K(t)
   // and V(t-2), whose last readers finished in step t-1.
+  // In the gather variant the ids of tiles kt and kt-2 must already be visible in the ids ring.
   auto issue_tiles = [&](int kt) {
     issue_one(kt, p.Kc, p.Kn, k_ring, k_offc, k_offn, false);
     if (kt >= 2) issue_one(kt - 2, p.Vc, p.Vn, v_ring, v_offc, v_offn, true);
@@ -355,6 +418,12 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnPara
   auto v_addr = [&](int tile) { return v_ring + (tile % kAtStages) * TILEB + v_off; };
 
   // ---- prologue: fill the ring (K tiles 0..S-1, V tiles 0..S-3), then S^T(0)
+  if (GATHER) {  // ids of the tiles whose loads are issued before step kAtIdLead's ids arrive
+#pragma unroll
+    for (int u = 0; u < kAtStages + kAtIdLead; ++u) issue_ids(u);
+    wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+  }
 #pragma unroll
   for (int u = 0; u < kAtStages; ++u) issue_tiles(u);  // tiles past the end hold clamped rows, never read back
   wait_vmcnt<0>();
@@ -380,18 +449,20 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnPara
   for (int T = 0; T < n_iter; ++T) {
     {
       const int t = 2 * T;
+      if (GATHER) issue_ids(t + kAtStages + kAtIdLead);
       issue_tiles(t + kAtStages);
       if ((t + 1) * kAtTileKeys > lim_min) attn_mask(s_a, t * kAtTileKeys, lim, g);
       attn_step<D>(s_a, s_b, p_b, p_a, o, qf, msc, l_run, k_addr(t + 1), v_addr(t > 0 ? t - 1 : 0), kx2, vx2, sc);
-      wait_vmcnt<2 * 2 * LPT>();
+      wait_vmcnt<2 * (2 * LPT + (GATHER ? 1 : 0))>();
       __builtin_amdgcn_s_barrier();
     }
     {
       const int t = 2 * T + 1;
+      if (GATHER) issue_ids(t + kAtStages + kAtIdLead);
       issue_tiles(t + kAtStages);
       if ((t + 1) * kAtTileKeys > lim_min) attn_mask(s_b, t * kAtTileKeys, lim, g);
       attn_step<D>(s_b, s_a, p_a, p_b, o, qf, msc, l_run, k_addr(T + 1 < n_iter ? t + 1 : t), v_addr(t - 1), kx2, vx2, sc);
-      wait_vmcnt<2 * 2 * LPT>();
+      wait_vmcnt<2 * (2 * LPT + (GATHER ? 1 : 0))>();
       __builtin_amdgcn_s_barrier();
     }
   }
@@ -428,25 +499,36 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnPara
   }
 }
 
-template <int D, bool OUT_F32>
+template <int D, bool OUT_F32, bool GATHER>
 int launch_variant(hipStream_t st, dim3 grid, const AttnParams& p) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(chunk_attention_kernel<D, OUT_F32>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, attn_lds_bytes(D));
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(chunk_attention_kernel<D, OUT_F32, GATHER>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, attn_lds_bytes(D, GATHER));
     if (e != hipSuccess) return record_hip_error(e);
     attr_set = true;
   }
-  hipLaunchKernelGGL((chunk_attention_kernel<D, OUT_F32>), grid, dim3(kAtThreads), attn_lds_bytes(D), st, p);
+  hipLaunchKernelGGL((chunk_attention_kernel<D, OUT_F32, GATHER>), grid, dim3(kAtThreads),
+                     attn_lds_bytes(D, GATHER), st, p);
   return check_launch();
+}
+
+template <bool GATHER>
+int launch_dims(hipStream_t st, dim3 grid, const AttnParams& p, int D, bool f32) {
+  if (D == 128)
+    return f32 ? launch_variant<128, true, GATHER>(st, grid, p) : launch_variant<128, false, GATHER>(st, grid, p);
+  return f32 ? launch_variant<64, true, GATHER>(st, grid, p) : launch_variant<64, false, GATHER>(st, grid, p);
 }
 
 }  // namespace
 
 int launch_attention(hipStream_t st, const void* Q, int Lq, const void* Kc, const void* Vc, int n_kept,
                      const void* Kn, const void* Vn, int Lc, int N, int D, long long ld_q, long long ld_c,
-                     long long ld_n, long long ld_o, int block_len, float scale, void* O, int out_dtype) {
+                     long long ld_n, long long ld_o, int block_len, float scale, void* O, int out_dtype,
+                     const int* ids, int n_cache) {
   AttnParams p;
+  p.ids = ids;
+  p.n_cache = n_cache;
   p.Q = static_cast<const unsigned short*>(Q);
   p.Kc = static_cast<const unsigned short*>(Kc);
   p.Vc = static_cast<const unsigned short*>(Vc);
@@ -457,10 +539,9 @@ int launch_attention(hipStream_t st, const void* Q, int Lq, const void* Kc, cons
   p.Lq = Lq; p.n_kept = n_kept; p.Lc = Lc;
   p.block_len = block_len < Lc ? block_len : Lc;  // blocks at least as long as the chunk mean "no mask"
   p.scale_log2 = scale * 1.44269504088896340736f;
-  const dim3 grid((Lq + kAtBQ - 1) / kAtBQ, N);
+  const dim3 grid(((Lq + kAtBQ - 1) / kAtBQ) * N);
   const bool f32 = out_dtype == PAFU_F32;
-  if (D == 128) return f32 ? launch_variant<128, true>(st, grid, p) : launch_variant<128, false>(st, grid, p);
-  return f32 ? launch_variant<64, true>(st, grid, p) : launch_variant<64, false>(st, grid, p);
+  return ids != nullptr && n_kept > 0 ? launch_dims<true>(st, grid, p, D, f32) : launch_dims<false>(st, grid, p, D, f32);
 }
 
 }  // namespace pafu

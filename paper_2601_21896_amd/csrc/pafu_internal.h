@@ -35,6 +35,7 @@ int launch_score(hipStream_t st, const void* x0, const void* x1, const void* x2,
                  int M, int n_out, int act, float* out, void* ws);
 int launch_attention(hipStream_t st, const void* Q, int Lq, const void* Kc, const void* Vc, int n_kept,
                      const void* Kn, const void* Vn, int Lc, int N, int D, long long ld_q, long long ld_c,
-                     long long ld_n, long long ld_o, int block_len, float scale, void* O, int out_dtype);
+                     long long ld_n, long long ld_o, int block_len, float scale, void* O, int out_dtype,
+                     const int* ids = nullptr, int n_cache = 0);
 
 }  // namespace pafu

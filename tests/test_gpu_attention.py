@@ -98,3 +98,51 @@ def test_attention_strided_slabs():
     want = orc.chunk_attention(Q, Kc, Vc, Kn, Vn, block_len=35)
     max_abs, rel = attn_errors(host(O), want)
     assert max_abs < ATTN_MAX_ABS and rel < ATTN_REL_FRO, (max_abs, rel)
+
+
+# ------------------------------------------------------------------ index-based Select (Sec. 3.4; Eq. 7)
+@pytest.mark.parametrize("n_cache,n_kept,Lc,N,D,L_B,order", [
+    (300, 128, 64, 2, 64, 64, "sorted"),       # retained rows = whole tiles
+    (300, 100, 64, 2, 64, 16, "sorted"),       # last cache tile mixed with chunk rows
+    (1000, 517, 200, 3, 128, 200, "sorted"),
+    (1000, 517, 200, 3, 128, 50, "shuffled"),  # the list need not be ascending
+    (500, 500, 130, 2, 128, 13, "sorted"),     # everything kept
+    (400, 0, 40, 1, 128, 7, "sorted"),         # nothing kept
+    (70, 1, 1, 1, 128, 1, "sorted"),
+    (5000, 2560, 300, 2, 128, 300, "sorted"),  # many full tiles through the prefetched-id path
+])
+def test_gather_attention_matches_oracle_and_the_compacted_path(n_cache, n_kept, Lc, N, D, L_B, order):
+    Q, Kc, Vc, Kn, Vn = _inputs(n_cache, Lc, N, D, seed=n_cache + n_kept)
+    rng = np.random.default_rng(n_cache * 3 + n_kept)
+    ids = np.sort(rng.permutation(n_cache)[:n_kept]).astype(np.int32)
+    if order == "shuffled":
+        ids = rng.permutation(ids).astype(np.int32)
+    d_ids = torch.from_numpy(ids).to(DEV) if n_kept else torch.zeros(4, dtype=torch.int32, device=DEV)
+    dQ, dKc, dVc, dKn, dVn = (dev(x, "bf16") for x in (Q, Kc, Vc, Kn, Vn))
+    O = torch.full((Lc + 2, N, D), 55.0, device=DEV, dtype=torch.bfloat16)
+    B.pafu_chunk_attention_gather(dQ, dKc, dVc, d_ids, n_kept, dKn, dVn, L_B, O[:Lc])
+    torch.cuda.synchronize()
+    assert torch.all(O[Lc:] == 55.0)
+    got = host(O[:Lc])
+    want = orc.chunk_attention(Q, Kc[ids], Vc[ids], Kn, Vn, block_len=L_B)
+    max_abs, rel = attn_errors(got, want)
+    assert max_abs < ATTN_MAX_ABS and rel < ATTN_REL_FRO, (max_abs, rel)
+    # same arithmetic in the same order as the plain kernel on the compacted cache: identical bits
+    plain = _run(Q, Kc[ids], Vc[ids], Kn, Vn, L_B)
+    assert np.array_equal(got, plain)
+
+
+def test_gather_attention_clamps_out_of_range_ids():
+    # ids outside the cache must not fault; rows are clamped into range (the result equals attention over those rows)
+    n_cache, Lc, N, D = 200, 64, 2, 128
+    Q, Kc, Vc, Kn, Vn = _inputs(n_cache, Lc, N, D, seed=5)
+    ids = np.arange(128, dtype=np.int32)
+    ids[3], ids[70] = -9, 10 ** 6
+    eff = np.clip(ids, 0, n_cache - 1)
+    O = torch.empty(Lc, N, D, device=DEV, dtype=torch.bfloat16)
+    B.pafu_chunk_attention_gather(dev(Q, "bf16"), dev(Kc, "bf16"), dev(Vc, "bf16"), torch.from_numpy(ids).to(DEV), 128,
+                                  dev(Kn, "bf16"), dev(Vn, "bf16"), Lc, O)
+    torch.cuda.synchronize()
+    want = orc.chunk_attention(Q, Kc[eff], Vc[eff], Kn, Vn, block_len=Lc)
+    max_abs, rel = attn_errors(host(O), want)
+    assert max_abs < ATTN_MAX_ABS and rel < ATTN_REL_FRO, (max_abs, rel)

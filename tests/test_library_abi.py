@@ -91,6 +91,18 @@ def test_attention_rejects_bad_arguments():
     assert call(od=5) == -3
     assert call(ldq=132) == -4
     assert call(O=A) == -6
+    g = lib.pafu_chunk_attention_gather
+
+    def gcall(n_cache=100, ids=A + 0x600000, nk=10, **kw):
+        a = dict(ok); a.update(kw)
+        return g(None, a["Q"], a["Lq"], a["Kc"], a["Vc"], n_cache, ids, nk, a["Kn"], a["Vn"], a["Lc"], a["N"], a["D"],
+                 a["ldq"], a["ldc"], a["ldn"], a["ldo"], a["LB"], a["sc"], a["O"], a["od"], None, 0)
+
+    assert gcall(nk=101) == -2                    # more retained rows than the cache holds
+    assert gcall(ids=None) == -1
+    assert gcall(ids=A + 0x600004) == -4
+    assert gcall(D=96) == -2
+    assert gcall(O=A + 0x100000) == -6            # output over the cache
 
 
 def test_score_rejects_bad_arguments():
