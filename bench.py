@@ -29,8 +29,8 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # HBM bytes per attention launch from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE, scaled by a copy kernel);
 # filled from the summaries under profiles/ (None = not measured for that workload).
 MEASURED_ATTENTION_TRAFFIC_BYTES = {
-    # profiles/step_C1_hbm_traffic_pmc.md: 512543.1 KiB x 1.98 fetched + 14040.8 KiB written
-    ("C1", True): int((512543.1 * 1.98 + 14040.8) * 1024),
+    # profiles/step_C1_hbm_traffic_pmc.md: 107168.7 KiB x 1.98 fetched + 14042.1 KiB written
+    ("C1", True): int((107168.7 * 1.98 + 14042.1) * 1024),
 }
 
 
