@@ -47,6 +47,9 @@ def parse():
     ap.add_argument("--sets", type=int, default=3, help="input buffer sets rotated between steps")
     ap.add_argument("--shared-index", action="store_true",
                     help="C2 only: score + select once on the last layer, every layer reuses its indices (Sec. 3.3)")
+    ap.add_argument("--head", default="benchmark", choices=["benchmark", "paper"],
+                    help="S-MLP widths: the benchmark's (F = H, M from the config, 1 output) or App. A's "
+                         "([Q|K|V] = 3H inputs, 1024 hidden, 12 outputs averaged)")
     ap.add_argument("--pinned", type=int, default=0, help="frame sink: cached tokens [0, pinned) are never evicted")
     return ap.parse_args()
 
@@ -158,6 +161,22 @@ def main():
     )
     W1 = to_dev(d["W1"], cfg.dtype == "bf16")
     W2, b1, b2 = to_dev(d["W2"]), None, None
+    paper_head = a.head == "paper"
+    n_seg = 3 if paper_head else 1
+    if paper_head:
+        # App. A "S-MLP": the head reads [Q | K | V] of the final layer (3 H features), 1024 hidden units, 12 outputs
+        # averaged.  Segments two and three are token-rolled copies of the generated features.
+        M = 1024
+        hw = wl.make_head_weights(wl.scaled(cfg, M=M, n_out=12), np.random.Generator(np.random.PCG64(wl.BASE_SEED + 77)),
+                                  F=3 * H, bias=True)
+        W1, b1, W2, b2 = to_dev(hw[0], True), to_dev(hw[1]), to_dev(hw[2]), to_dev(hw[3])
+
+    def feature_segments(X):
+        if not paper_head:
+            return (X[:n],), (X[n:],)
+        segs = [X, torch.cat([torch.roll(X[:n], 311, 0), torch.roll(X[n:], 311, 0)]),
+                torch.cat([torch.roll(X[:n], 733, 0), torch.roll(X[n:], 733, 0)])]
+        return tuple(t[:n] for t in segs), tuple(t[n:] for t in segs)
     n_sets = max(1, a.sets) if n_layers == 1 else 1
     sets = []
     for s in range(n_sets * n_layers):
@@ -173,10 +192,14 @@ def main():
                    K_out=torch.empty(max(n_kept, 1), N, D, device=dev, dtype=bf),
                    V_out=torch.empty(max(n_kept, 1), N, D, device=dev, dtype=bf),
                    SL_out=torch.empty(max(n_kept, 1), device=dev), O=torch.empty(Lc, N, D, device=dev, dtype=bf))
-        cur["args"] = B.make_step_args(B.PAFU_MODE_SINGLE, N, D, n, Lc, k, L_B, cur["X"][:n], cur["X"][n:], W1, b1, W2,
-                                       b2, cur["K"], cur["V"], None, cur["Q"], cur["Kn"], cur["Vn"], cur["scores"],
+        cur["x_cache"], cur["x_chunk"] = feature_segments(cur["X"])
+        cur["x_all"] = tuple(torch.cat([c_, n_]) for c_, n_ in zip(cur["x_cache"], cur["x_chunk"])) if paper_head \
+            else (cur["X"],)
+        cur["ws"] = torch.empty(M + 64, device=dev)
+        cur["args"] = B.make_step_args(B.PAFU_MODE_SINGLE, N, D, n, Lc, k, L_B, cur["x_cache"], cur["x_chunk"], W1, b1,
+                                       W2, b2, cur["K"], cur["V"], None, cur["Q"], cur["Kn"], cur["Vn"], cur["scores"],
                                        cur["ids"], cur["K_out"], cur["V_out"], cur["SL_out"], cur["O"],
-                                       n_pinned=a.pinned)
+                                       workspace=cur["ws"], n_pinned=a.pinned)
         sets.append(cur)
     torch.cuda.synchronize()
     gen_s = time.time() - t0
@@ -210,7 +233,7 @@ def main():
 
     def stage_calls(cur):
         return (
-            lambda: B.pafu_score(cur["X"], W1, b1, W2, b2, cur["scores"]),
+            lambda: B.pafu_score(cur["x_all"], W1, b1, W2, b2, cur["scores"], workspace=cur["ws"]),
             lambda: B.pafu_select_topk(cur["scores"], k, cur["ids"], n=n),
             lambda: B.pafu_compact_kv(cur["K"], cur["V"], cur["scores"], cur["ids"], n_kept, cur["K_out"], cur["V_out"],
                                       cur["SL_out"]),
@@ -243,14 +266,15 @@ def main():
     eb = 2 if cfg.dtype == "bf16" else 4
     visible_pairs = Lc * n_kept + sum(min(Lc, (i // L_B + 1) * L_B) for i in range(Lc))
     attn_flops = 4.0 * visible_pairs * D * N
-    bytes_score = T * H * eb + M * H * eb + T * 4
+    F_in = n_seg * H
+    bytes_score = T * F_in * eb + M * F_in * eb + T * 4
     bytes_select = n * 4 + n_kept * 4
     bytes_compact = 2 * (2 * n_kept * N * D * 2) + 2 * n_kept * 4 + n_kept * 4
     attn_tflops = attn_flops / (avg["attention"] * 1e-3) / 1e12
     stages = {
         "score": {"ms": avg["score"], "min_ms": mn["score"], "GB/s": bytes_score / avg["score"] / 1e6,
                   "frac_hbm": bytes_score / avg["score"] / 1e6 / PEAK_HBM_GBS,
-                  "TFLOP/s": 2.0 * T * H * M / avg["score"] / 1e9},
+                  "TFLOP/s": 2.0 * T * F_in * M / avg["score"] / 1e9},
         "select": {"ms": avg["select"], "min_ms": mn["select"], "GB/s": bytes_select / avg["select"] / 1e6},
         "compact": {"ms": avg["compact"], "min_ms": mn["compact"], "GB/s": bytes_compact / avg["compact"] / 1e6,
                     "frac_hbm": bytes_compact / avg["compact"] / 1e6 / PEAK_HBM_GBS},
@@ -264,7 +288,7 @@ def main():
 
     # ---- CPU baseline: the oracle as it stands, bounded sample of the same workload
     cpu = None
-    if not a.no_cpu_baseline and a.workload in ("C1", "C0", "C2"):
+    if not a.no_cpu_baseline and a.workload in ("C1", "C0", "C2") and not paper_head:
         from oracle import pafu_oracle as orc
         try:
             from threadpoolctl import threadpool_info
@@ -298,8 +322,9 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": "%s: %d layer(s), %d heads x %d, cache %d tokens, chunk %d queries, budget %d, "
-                               "S-MLP %d->%d->%d, L_B=%d, salient=%s" % (a.workload, n_layers, N, D, n, Lc, k, H, M,
-                                                                          cfg.n_out, L_B, a.structure),
+                               "S-MLP %d->%d->%d, L_B=%d, salient=%s" % (a.workload, n_layers, N, D, n, Lc, k, F_in, M,
+                                                                          12 if paper_head else cfg.n_out, L_B,
+                                                                          a.structure),
                    "layers": n_layers, "input_sets": n_sets,
                    "indices": "shared (last layer's head)" if (a.shared_index and n_layers > 1) else "per layer",
                    "n_pinned": a.pinned},
