@@ -38,6 +38,7 @@ __all__ = [
     "rollout_step",
     "step_single_shared",
     "rollout_step_shared",
+    "sse_score",
 ]
 
 
@@ -309,3 +310,57 @@ def rollout_step_shared(states, index_layer: int, X_chunk, W1, b1, W2, b2, chunk
         st.V = np.concatenate([Vk, np.asarray(c["V_chunk"], dtype=Vk.dtype)], axis=0)
     states[index_layer].SL = np.concatenate([SL[ids], s32]).astype(np.float32)
     return dict(s_chunk=s_chunk, ids=ids, O=Os)
+
+
+# --------------------------------------------------------------------------------------
+# Spatialtemporal-balanced Salience Estimation (teacher-side score), Sec. 3.2, Eq. 4-5
+# --------------------------------------------------------------------------------------
+def sse_score(Q, K, block_len: int, scale: float | None = None, return_parts: bool = False):
+    """Salience score of every key from the attention weights of a bidirectional pass.
+
+    Sec. 3.2: P = softmax(Q K^T / sqrt(D)) over the FULL key axis, per head.  With blocks of
+    L_B tokens, b(i) = floor(i / L_B), the queries of key j fall into three sets: those in a
+    later block than j ("low": j < l(i)), in j's own block ("diag") and in an earlier block
+    ("up": j >= h(i)).  Eq. 4: per set, the maximum of P[h, i, j] over its queries, then the
+    mean over heads.  Eq. 5: the score is the mean of the parts that exist for the key -
+    (diag + low) / 2 in the first block, (up + diag + low) / 3 in the middle, (diag + up) / 2
+    in the last block.
+
+    Readings: the sum in Eq. 4 runs over heads; the block-wise listing in the appendix differs
+    from Eq. 4-5 (no softmax, mean over heads before the maximum) and is not followed; a part
+    "exists" for key j iff its query set is non-empty, which is Eq. 5 whenever the sequence is a
+    whole number (>= 2) of blocks and extends it to a single block (score = diag) and to a
+    ragged last block.
+
+    Q, K: [L, N, D].  returns s [L] float64 (and low, diag, up [L] with return_parts; a part
+    whose query set is empty is 0 there).
+    """
+    Q = np.asarray(Q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    L, N, D = Q.shape
+    assert K.shape == (L, N, D) and block_len >= 1
+    scale = 1.0 / math.sqrt(D) if scale is None else float(scale)
+    blk = np.arange(L) // int(block_len)
+    later = blk[:, None] > blk[None, :]      # [i, j]: query i sits in a later block than key j
+    same = blk[:, None] == blk[None, :]
+    earlier = blk[:, None] < blk[None, :]
+    low = np.zeros(L)
+    diag = np.zeros(L)
+    up = np.zeros(L)
+    for h in range(N):
+        z = (Q[:, h, :] @ K[:, h, :].T) * scale            # [i, j]
+        z -= z.max(axis=1, keepdims=True)
+        P = np.exp(z)
+        P /= P.sum(axis=1, keepdims=True)
+        low += np.where(later, P, 0.0).max(axis=0)          # P > 0, so an empty set gives 0
+        diag += np.where(same, P, 0.0).max(axis=0)
+        up += np.where(earlier, P, 0.0).max(axis=0)
+    low /= N
+    diag /= N
+    up /= N
+    has_low = blk < blk[-1]
+    has_up = blk > 0
+    s = (diag + np.where(has_low, low, 0.0) + np.where(has_up, up, 0.0)) / (1.0 + has_low + has_up)
+    if return_parts:
+        return s, low, diag, up
+    return s
