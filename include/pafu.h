@@ -147,6 +147,24 @@ int pafu_chunk_attention_gather(void* stream, const void* Q, int Lq, const void*
                                 size_t workspace_bytes);
 
 /* ------------------------------------------------------------------------------------------
+ * pafu_sse_score - Spatialtemporal-balanced Salience Estimation, the teacher-side score that the Salience
+ * Estimation Head is trained to predict (Sec. 3.2, Eq. 4-5).
+ *
+ *   P = softmax(scale * Q K^T) per head over all L keys (no mask: a bidirectional pass).  b(i) = floor(i/block_len).
+ *   low[j]  = mean_h max_{i : b(i) > b(j)} P[h,i,j]     diag[j] = mean_h max_{i : b(i) = b(j)} P[h,i,j]
+ *   up[j]   = mean_h max_{i : b(i) < b(j)} P[h,i,j]
+ *   s[j]    = mean of the parts whose query set is not empty: (diag+low)/2 in the first block, (up+diag+low)/3 in
+ *             the middle, (diag+up)/2 in the last block (Eq. 5); a single block gives diag.
+ *   Q, K : [L, N, D] bf16, strides ld_q / ld_k elements (each tensor must span less than 4 GiB)
+ *   out  : [L] fp32       D must be 64 or 128       softmax_scale <= 0 means 1/sqrt(D)
+ *   workspace : pafu_sse_workspace_bytes(L, N) bytes (per-query softmax normalisers and per-head partial maxima)
+ * The L x L matrix is never materialised.  L == 0 is a no-op.
+ */
+size_t pafu_sse_workspace_bytes(int L, int N);
+int pafu_sse_score(void* stream, const void* Q, const void* K, int L, int N, int D, long long ld_q, long long ld_k,
+                   int block_len, float softmax_scale, float* out, void* workspace, size_t workspace_bytes);
+
+/* ------------------------------------------------------------------------------------------
  * pafu_step - one chunk step of one layer on one stream, Alg. 2; Sec. 3.4.
  *
  * SINGLE : scores the n cached tokens and the Lc chunk tokens (scores[0:n], scores[n:n+Lc]),

@@ -25,6 +25,7 @@ SYMBOLS = (
     "pafu_select_workspace_bytes", "pafu_select_topk", "pafu_select_topk_pinned",
     "pafu_compact_kv",
     "pafu_attention_workspace_bytes", "pafu_chunk_attention", "pafu_chunk_attention_gather",
+    "pafu_sse_workspace_bytes", "pafu_sse_score",
     "pafu_step_workspace_bytes", "pafu_step", "pafu_step_layers", "pafu_step_layers_shared",
 )
 
@@ -103,6 +104,11 @@ def _lib():
         lib.pafu_step.argtypes = [c_void_p, POINTER(pafu_step_args)]
         lib.pafu_step_layers.restype = c_int
         lib.pafu_step_layers.argtypes = [c_void_p, POINTER(pafu_step_args), c_int]
+        lib.pafu_sse_workspace_bytes.restype = c_size_t
+        lib.pafu_sse_workspace_bytes.argtypes = [c_int, c_int]
+        lib.pafu_sse_score.restype = c_int
+        lib.pafu_sse_score.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_longlong, c_longlong, c_int,
+                                       c_float, c_void_p, c_void_p, c_size_t]
         lib.pafu_step_layers_shared.restype = c_int
         lib.pafu_step_layers_shared.argtypes = [c_void_p, POINTER(pafu_step_args), c_int, c_int]
         _LIB = lib
@@ -286,3 +292,17 @@ def pafu_step_layers_shared(args_list, index_layer, stream=None):
     arr = (pafu_step_args * len(args_list))(*args_list)
     _check(_lib().pafu_step_layers_shared(_stream(stream), arr, len(args_list), index_layer),
            "pafu_step_layers_shared")
+
+
+def pafu_sse_workspace_bytes(L: int, N: int) -> int:
+    return _lib().pafu_sse_workspace_bytes(L, N)
+
+
+def pafu_sse_score(Q, K, block_len, out, workspace, softmax_scale=0.0, stream=None):
+    """Q, K: [L, N, D] bf16; out: [L] fp32; workspace: at least pafu_sse_workspace_bytes(L, N) bytes."""
+    L, N, D = Q.shape
+    rc = _lib().pafu_sse_score(_stream(stream), _ptr(Q), _ptr(K), L, N, D, Q.stride(0), K.stride(0), block_len,
+                               float(softmax_scale), _ptr(out), _ptr(workspace),
+                               workspace.numel() * workspace.element_size())
+    _check(rc, "pafu_sse_score")
+    return out

@@ -320,6 +320,32 @@ int pafu_chunk_attention_gather(void* stream, const void* Q, int Lq, const void*
                           ld_c, ld_n, ld_o, block_len, scale, O, out_dtype, ids, n_cache);
 }
 
+size_t pafu_sse_workspace_bytes(int L, int N) { return L > 0 && N > 0 ? sse_workspace_bytes(L, N) : 0; }
+
+int pafu_sse_score(void* stream, const void* Q, const void* K, int L, int N, int D, long long ld_q, long long ld_k,
+                   int block_len, float softmax_scale, float* out, void* workspace, size_t workspace_bytes) {
+  if (L < 0 || N < 1 || N > 65535 || block_len < 1) return PAFU_ERR_SHAPE;
+  if (D != 64 && D != 128) return PAFU_ERR_SHAPE;
+  if (L == 0) return PAFU_OK;
+  if (!Q || !K || !out) return PAFU_ERR_NULL;
+  const long long row = (long long)N * D;
+  if (ld_q < row || ld_k < row) return PAFU_ERR_SHAPE;
+  // rows are addressed by 32-bit byte offsets from the head's base
+  if ((long long)L * ld_q * 2 >= (1ll << 32) || (long long)L * ld_k * 2 >= (1ll << 32)) return PAFU_ERR_SHAPE;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(out) || !aligned16(workspace) || (ld_q * 2) % 16 != 0 ||
+      (ld_k * 2) % 16 != 0)
+    return PAFU_ERR_ALIGN;
+  if (!workspace || workspace_bytes < sse_workspace_bytes(L, N)) return PAFU_ERR_WORKSPACE;
+  const size_t o_bytes = (size_t)L * 4;
+  if (overlaps(out, o_bytes, Q, (size_t)L * ld_q * 2) || overlaps(out, o_bytes, K, (size_t)L * ld_k * 2) ||
+      overlaps(out, o_bytes, workspace, workspace_bytes) ||
+      overlaps(workspace, workspace_bytes, Q, (size_t)L * ld_q * 2) ||
+      overlaps(workspace, workspace_bytes, K, (size_t)L * ld_k * 2))
+    return PAFU_ERR_ALIAS;
+  const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)D);
+  return launch_sse(static_cast<hipStream_t>(stream), Q, K, L, N, D, ld_q, ld_k, block_len, scale, out, workspace);
+}
+
 size_t pafu_step_workspace_bytes(const pafu_step_args* a) {
   if (!a) return 0;
   return a->n_out > 1 ? align_up(pafu_score_workspace_bytes(a->M)) : 0;

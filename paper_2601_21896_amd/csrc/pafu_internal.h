@@ -33,6 +33,9 @@ int launch_select(hipStream_t st, const float* scores, int n, int k, int n_pinne
 int launch_score(hipStream_t st, const void* x0, const void* x1, const void* x2, int n_seg, int T, int Fs,
                  long long ld_x, int x_dtype, const void* W1, const float* b1, const float* W2, const float* b2,
                  int M, int n_out, int act, float* out, void* ws);
+size_t sse_workspace_bytes(int L, int N);
+int launch_sse(hipStream_t st, const void* Q, const void* K, int L, int N, int D, long long ld_q, long long ld_k,
+               int block_len, float scale, float* out, void* workspace);
 int launch_attention(hipStream_t st, const void* Q, int Lq, const void* Kc, const void* Vc, int n_kept,
                      const void* Kn, const void* Vn, int Lc, int N, int D, long long ld_q, long long ld_c,
                      long long ld_n, long long ld_o, int block_len, float scale, void* O, int out_dtype,

@@ -1,0 +1,107 @@
+"""GPU parity of pafu_sse_score (Sec. 3.2, Eq. 4-5) against the fp64 oracle, through the C ABI.
+
+Tolerance: the kernel computes q.k with fp32 accumulation of exact bf16 products (error ~1e-6 relative to |z| <= ~30
+in the exponent), the exponential and the logarithm with the hardware's base-2 units (~1 ulp) and sums L terms in
+fp32: the weights come out within ~1e-4 relative.  The test allows 1e-3 relative plus 1e-9 absolute."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import pafu_oracle as orc
+from paper_2601_21896_amd import binding as B
+from paper_2601_21896_amd import workloads as wl
+from tests.gpu_util import DEV, dev, host
+
+pytestmark = pytest.mark.gpu
+
+RTOL, ATOL = 1e-3, 1e-9
+
+
+def _run(Q, K, L_B, scale=0.0, pad=0):
+    L, N, D = Q.shape
+    if pad:
+        Qs = torch.zeros(L, N * D + pad, device=DEV, dtype=torch.bfloat16)
+        Ks = torch.zeros(L, N * D + pad, device=DEV, dtype=torch.bfloat16)
+        Qs[:, :N * D] = dev(Q, "bf16").reshape(L, N * D)
+        Ks[:, :N * D] = dev(K, "bf16").reshape(L, N * D)
+        dQ = Qs.as_strided((L, N, D), (N * D + pad, D, 1))
+        dK = Ks.as_strided((L, N, D), (N * D + pad, D, 1))
+    else:
+        dQ, dK = dev(Q, "bf16"), dev(K, "bf16")
+    out = torch.full((L + 4,), -3.0, device=DEV)
+    ws = torch.empty(B.pafu_sse_workspace_bytes(L, N) // 4 + 4, device=DEV)
+    B.pafu_sse_score(dQ, dK, L_B, out[:L], ws, softmax_scale=scale)
+    torch.cuda.synchronize()
+    assert torch.all(out[L:] == -3.0)
+    return host(out[:L])
+
+
+def _qk(L, N, D, seed, gain=1.0):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    Q = wl.round_to_bf16((rng.standard_normal((L, N, D), dtype=np.float32) * np.float32(gain)))
+    K = wl.round_to_bf16(rng.standard_normal((L, N, D), dtype=np.float32))
+    return Q, K
+
+
+@pytest.mark.parametrize("L,N,D,L_B,gain", [
+    (256, 2, 64, 64, 1.0),        # whole tiles, blocks aligned to tiles
+    (256, 2, 128, 64, 1.0),
+    (300, 3, 128, 100, 1.0),      # ragged tiles, blocks cut tiles and 32-key groups
+    (777, 2, 128, 111, 2.0),      # block length not a multiple of 4: every boundary tile takes the per-element path
+    (520, 2, 64, 130, 1.0),
+    (1000, 2, 128, 1000, 1.0),    # one block: the score is the diagonal part
+    (1000, 2, 128, 5000, 3.0),    # block longer than the sequence
+    (2048, 4, 128, 512, 2.0),
+    (70, 1, 128, 8, 1.0),         # many short blocks
+    (1, 1, 128, 1, 1.0),
+    (33, 2, 64, 1, 1.0),          # every token its own block
+    (4680, 2, 128, 1560, 1.5),    # three frames of the video model, one block per frame
+])
+def test_sse_matches_oracle(L, N, D, L_B, gain):
+    Q, K = _qk(L, N, D, seed=L + L_B, gain=gain)
+    got = _run(Q, K, L_B)
+    want = orc.sse_score(Q, K, L_B)
+    assert np.all(np.abs(got - want) <= RTOL * np.abs(want) + ATOL), np.abs(got - want).max()
+    assert want.max() > 5e-3           # the scores are not all negligible
+
+
+def test_sse_strided_inputs_and_explicit_scale():
+    Q, K = _qk(400, 2, 128, seed=9)
+    got = _run(Q, K, 100, scale=0.05, pad=24)
+    want = orc.sse_score(Q, K, 100, scale=0.05)
+    assert np.all(np.abs(got - want) <= RTOL * np.abs(want) + ATOL)
+
+
+def test_sse_uniform_attention_closed_form_at_full_size():
+    # Q = 0: every weight is 1/L, so every part that exists and the score are 1/L (Wan-1.3B teacher shape:
+    # 21 frames x 1560 tokens, 12 heads, blocks of 3 frames)
+    L, N, D, L_B = 32760, 12, 128, 4680
+    K = torch.randn(L, N, D, device=DEV).to(torch.bfloat16)
+    Q = torch.zeros(L, N, D, device=DEV, dtype=torch.bfloat16)
+    out = torch.empty(L, device=DEV)
+    ws = torch.empty(B.pafu_sse_workspace_bytes(L, N) // 4, device=DEV)
+    B.pafu_sse_score(Q, K, L_B, out, ws)
+    torch.cuda.synchronize()
+    got = host(out)
+    assert np.all(np.abs(got - 1.0 / L) <= 1e-4 / L)
+
+
+def test_sse_periodic_keys_closed_form_at_full_size():
+    # q_i = k_i = a * e_(i mod 64): z_ij = a^2 / sqrt(D) when i = j (mod 64), else 0.  A row has L/64 matching keys
+    # (L a multiple of 64), so P_ij = E / (m E + L - m) for matches with E = exp(a^2 / sqrt(D)), m = L / 64, and
+    # every key has matching queries in earlier, own and later blocks: all parts, hence the score, equal that value.
+    L, N, D, L_B, a = 32768, 2, 128, 4096, 8.0
+    idx = torch.arange(L, device=DEV) % 64
+    X = torch.zeros(L, N, D, device=DEV, dtype=torch.bfloat16)
+    X[torch.arange(L, device=DEV), :, idx] = a
+    out = torch.empty(L, device=DEV)
+    ws = torch.empty(B.pafu_sse_workspace_bytes(L, N) // 4, device=DEV)
+    B.pafu_sse_score(X, X, L_B, out, ws)
+    torch.cuda.synchronize()
+    E = math.exp(a * a / math.sqrt(D))
+    m = L // 64
+    want = E / (m * E + L - m)
+    got = host(out)
+    assert np.all(np.abs(got - want) <= RTOL * want)

@@ -141,3 +141,28 @@ def test_step_rejects_bad_arguments():
     a.n_pinned = -1
     a.Lc = a.N = a.D = 1
     assert lib.pafu_step(None, ctypes.byref(a)) == -2                             # negative frame sink
+
+
+def test_sse_rejects_bad_arguments_and_reports_its_workspace():
+    lib = binding.library()
+    assert binding.pafu_sse_workspace_bytes(1000, 3) == 16 * 3 * 1000
+    f = lib.pafu_sse_score
+    ok = dict(Q=A, K=A + 0x100000, L=100, N=2, D=64, ldq=128, ldk=128, LB=10, sc=0.0, out=A + 0x200000,
+              ws=A + 0x300000, wsb=16 * 2 * 100)
+
+    def call(**kw):
+        a = dict(ok); a.update(kw)
+        return f(None, a["Q"], a["K"], a["L"], a["N"], a["D"], a["ldq"], a["ldk"], a["LB"], a["sc"], a["out"], a["ws"],
+                 a["wsb"])
+
+    assert call(D=96) == -2
+    assert call(LB=0) == -2
+    assert call(L=-1) == -2
+    assert call(L=0) == 0                          # nothing to do
+    assert call(Q=None) == -1
+    assert call(out=None) == -1
+    assert call(ldq=100) == -2                     # stride shorter than a token
+    assert call(ldq=132) == -4
+    assert call(wsb=100) == -5
+    assert call(ws=None) == -5
+    assert call(out=A + 0x300000) == -6            # output inside the workspace
