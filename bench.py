@@ -34,12 +34,49 @@ MEASURED_ATTENTION_TRAFFIC_BYTES = {
 }
 
 
+def sse(a, torch, np, B, wl):
+    """Teacher-side salience score (Sec. 3.2, Eq. 4-5) at the Wan-1.3B teacher shape: 21 frames x 1560 tokens,
+    12 heads x 128, blocks of 3 frames.  Not the headline metric: a second measured workload."""
+    cfg = wl.C1
+    L, N, D, L_B = cfg.n, cfg.N, cfg.D, a.block_len or cfg.Lc
+    dev = "cuda:0"
+    rng = np.random.Generator(np.random.PCG64(wl.BASE_SEED + 9))
+    c = rng.uniform(0.5, 2.0, size=(N * D,)).astype(np.float32)
+    sets = []
+    for s_ in range(2):
+        Q = torch.from_numpy(rng.standard_normal((L, N * D), dtype=np.float32)).to(dev).to(torch.bfloat16)
+        K = (torch.from_numpy(rng.standard_normal((L, N * D), dtype=np.float32)) * torch.from_numpy(c)).to(dev)
+        sets.append((Q.view(L, N, D), K.to(torch.bfloat16).view(L, N, D)))
+    out = torch.empty(L, device=dev)
+    ws = torch.empty(B.pafu_sse_workspace_bytes(L, N) // 4, device=dev)
+    for i in range(a.warmup):
+        B.pafu_sse_score(sets[i % 2][0], sets[i % 2][1], L_B, out, ws)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(a.steps):
+        B.pafu_sse_score(sets[i % 2][0], sets[i % 2][1], L_B, out, ws)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / a.steps
+    flops = 2 * 2.0 * L * L * D * N          # two passes over Q K^T
+    print(json.dumps({
+        "metric": "ms per SSE salience score (Eq. 4-5)", "value": ms, "unit": "ms", "n_gpus": 1, "steps": a.steps,
+        "warmup": a.warmup, "ms_per_step": ms, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "SSE: %d tokens (21 frames x 1560), %d heads x %d, L_B=%d" % (L, N, D, L_B)},
+        "roofline": {"kernel": "sse_pass_kernel (both passes)", "bound": "mfma", "achieved": flops / ms / 1e9,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": flops / ms / 1e9 / PEAK_BF16_TFLOPS,
+                     "traffic": None, "flops_per_launch": flops},
+        "cpu_baseline": None}))
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="C1", choices=["C1", "C4", "C2", "C0", "C3"])
+    ap.add_argument("--workload", default="C1", choices=["C1", "C4", "C2", "C0", "C3", "SSE"])
     ap.add_argument("--budget", type=int, default=0, help="C3 only: cache budget k in tokens (default 8 frames = 12480)")
     ap.add_argument("--block-len", type=int, default=0, help="L_B (0 = chunk length, the paper's setting)")
     ap.add_argument("--structure", default="uniform", choices=["uniform", "coherent"])
@@ -136,6 +173,9 @@ def main():
 
     if a.workload == "C3":
         rollout(a, torch, np, B, wl)
+        return
+    if a.workload == "SSE":
+        sse(a, torch, np, B, wl)
         return
     n_layers = wl.C2_LAYERS if a.workload == "C2" else 1
     cfg = wl.C1 if a.workload == "C2" else wl.CONFIGS[a.workload]
