@@ -32,7 +32,6 @@ typedef __attribute__((address_space(3))) unsigned char lds_byte;
 
 constexpr int kSseWaves = 8;
 constexpr int kSseThreads = kSseWaves * 64;
-constexpr int kSseHeld = kSseWaves * 32;  // held rows (queries in rowstat, keys in colmax) per workgroup
 constexpr int kSseTile = 64;              // streamed rows per LDS tile = per step
 constexpr int kSseStages = 4;             // ring depth
 constexpr int kSseXcds = 8;
@@ -78,9 +77,10 @@ __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
-// COLMAX = false: rowstat.  COLMAX = true: colmax.
-template <int D, bool COLMAX>
-__global__ __launch_bounds__(kSseThreads, 2) void sse_pass_kernel(SseParams p) {
+// COLMAX = false: rowstat.  COLMAX = true: colmax.  HT = 32-row groups of the held tensor per wave: every A fragment
+// read from LDS feeds HT matrix instructions.
+template <int D, bool COLMAX, int HT>
+__global__ __launch_bounds__(kSseThreads, HT == 1 ? 2 : 1) void sse_pass_kernel(SseParams p) {
   constexpr int ROWB = 2 * D;               // bytes per row of one head
   constexpr int TILEB = kSseTile * ROWB;    // bytes per streamed tile
   constexpr int CH = D / 8;                 // 16-byte chunks per row
@@ -89,6 +89,7 @@ __global__ __launch_bounds__(kSseThreads, 2) void sse_pass_kernel(SseParams p) {
   constexpr int LPT = TILEB / 1024 / kSseWaves;
   constexpr int KD = D / 16;
   constexpr int LOADS = LPT + (COLMAX ? 1 : 0);  // vector-memory loads per wave per tile
+  constexpr int HELD = kSseWaves * 32 * HT;      // held rows per workgroup
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds_raw[];
   lds_byte* const ring = (lds_byte*)lds_raw;
   lds_byte* const c_ring = ring + kSseStages * TILEB;  // 64 floats per stage (colmax)
@@ -97,22 +98,23 @@ __global__ __launch_bounds__(kSseThreads, 2) void sse_pass_kernel(SseParams p) {
   const int g = lane >> 5, c = lane & 31;
   const int L = p.L;
   // workgroup -> (head, held tile), one contiguous range of the head-major list per XCD (each has its own L2)
-  const int n_ht = (L + kSseHeld - 1) / kSseHeld;
+  const int n_ht = (L + HELD - 1) / HELD;
   const int total = gridDim.x;
   const int xcd = blockIdx.x % kSseXcds, slot = blockIdx.x / kSseXcds;
   const int work = xcd * (total / kSseXcds) + (xcd < total % kSseXcds ? xcd : total % kSseXcds) + slot;
   const int h = work / n_ht;
-  const int held0 = (work - h * n_ht) * kSseHeld + wave * 32;  // first held row of this wave
-  const int my_row = held0 + c;                                // this lane's held row (may be >= L)
+  const int held0 = (work - h * n_ht) * HELD + wave * 32 * HT;  // first held row of this wave
   const int n_tiles = (L + kSseTile - 1) / kSseTile;
 
-  // ---- held fragments (B operand): lane (row c, half g) holds held[row][16 kk + 8 g .. + 8]
-  bf16x8 hf[KD];
-  {
+  // ---- held fragments (B operand): lane (row c of group ht, half g) holds held[row][16 kk + 8 g .. + 8]
+  bf16x8 hf[HT][KD];
+#pragma unroll
+  for (int ht = 0; ht < HT; ++ht) {
+    const int my_row = held0 + 32 * ht + c;  // may be >= L
     const int r = my_row < L ? my_row : L - 1;
     const unsigned short* hp = p.held + (long long)r * p.ld_held + (long long)h * D + 8 * g;
 #pragma unroll
-    for (int kk = 0; kk < KD; ++kk) hf[kk] = *reinterpret_cast<const bf16x8*>(hp + 16 * kk);
+    for (int kk = 0; kk < KD; ++kk) hf[ht][kk] = *reinterpret_cast<const bf16x8*>(hp + 16 * kk);
   }
 
   // ---- streamed tile loads: load j of this wave fills tile rows (wave + W j) RPI .. + RPI; lane -> (row, slot);
@@ -147,14 +149,18 @@ __global__ __launch_bounds__(kSseThreads, 2) void sse_pass_kernel(SseParams p) {
 
   const float sc = p.scale_log2;
   // rowstat state: running maximum and sum of this lane's half of the keys
-  float m_run = -INFINITY, l_run = 0.f;
+  float m_run[HT], l_run[HT];
   // colmax state: maxima of z - c over the queries seen so far, by block relation
-  float mx_low = -INFINITY, mx_diag = -INFINITY, mx_up = -INFINITY;
-  // this lane's key block [lo, hi) in query rows (colmax), and the extremes over the wave's 32 keys
+  float mx_low[HT], mx_diag[HT], mx_up[HT];
+#pragma unroll
+  for (int ht = 0; ht < HT; ++ht) {
+    m_run[ht] = -INFINITY; l_run[ht] = 0.f;
+    mx_low[ht] = -INFINITY; mx_diag[ht] = -INFINITY; mx_up[ht] = -INFINITY;
+  }
+  // the extremes of the key blocks [lo, hi) (in query rows) over the wave's keys (colmax)
   const int L_B = p.block_len;
-  const int my_lo = (my_row / L_B) * L_B, my_hi = my_lo + L_B;
   const int w_lo_min = (held0 / L_B) * L_B;
-  const int w_last = held0 + 31 < L ? held0 + 31 : L - 1;
+  const int w_last = held0 + 32 * HT - 1 < L ? held0 + 32 * HT - 1 : L - 1;
   const int w_lo_max = (w_last / L_B) * L_B;
   const int w_hi_min = w_lo_min + L_B, w_hi_max = w_lo_max + L_B;
 
@@ -167,43 +173,50 @@ __global__ __launch_bounds__(kSseThreads, 2) void sse_pass_kernel(SseParams p) {
   for (int t = 0; t < n_tiles; ++t) {
     issue(t + kSseStages - 1);  // into the slot tile t-1 vacated (tiles past the end hold clamped rows, never used)
     const lds_byte* st = ring + (t % kSseStages) * TILEB + a_off;
-    f32x16 s[2];
+    f32x16 s[HT][2];
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
+    for (int ht = 0; ht < HT; ++ht)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[rb][r] = 0.f;
+      for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[ht][rb][r] = 0.f;
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
       for (int kk = 0; kk < KD; ++kk) {
         const bf16x8 a = *(const __attribute__((address_space(3))) bf16x8*)(st + rb * 32 * ROWB + (((2 * kk) ^ kx2) << 4));
-        s[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, hf[kk], s[rb], 0, 0, 0);
+#pragma unroll
+        for (int ht = 0; ht < HT; ++ht) s[ht][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, hf[ht][kk], s[ht][rb], 0, 0, 0);
       }
-    }
-    // register r of s[rb] is streamed row  t 64 + 32 rb + 8 (r/4) + 4 g + (r%4)  against this lane's held row
+    // register r of s[ht][rb] is streamed row  t 64 + 32 rb + 8 (r/4) + 4 g + (r%4)  against held row 32 ht + c
     const int row0 = t * kSseTile;
     if (!COLMAX) {
       // ---- online log-sum-exp over the keys
-      if (row0 + kSseTile > L) {  // ragged last tile: keys past the end do not exist
+#pragma unroll
+      for (int ht = 0; ht < HT; ++ht) {
+        if (row0 + kSseTile > L) {  // ragged last tile: keys past the end do not exist
+#pragma unroll
+          for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+              if (row0 + 32 * rb + 8 * (r >> 2) + 4 * g + (r & 3) >= L) s[ht][rb][r] = -INFINITY;
+        }
+        float tmax = s[ht][0][0];
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-          for (int r = 0; r < 16; ++r)
-            if (row0 + 32 * rb + 8 * (r >> 2) + 4 * g + (r & 3) >= L) s[rb][r] = -INFINITY;
+          for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[ht][rb][r]);
+        const float m_new = fmaxf(m_run[ht], tmax * sc);  // sc > 0
+        float sum = 0.f;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(fmaf(s[ht][rb][r], sc, -m_new));
+        // a ragged tail can leave this half of the lanes without a real key: then everything is -inf and nothing
+        // may change
+        l_run[ht] = (m_new == -INFINITY) ? 0.f : fmaf(l_run[ht], __builtin_amdgcn_exp2f(m_run[ht] - m_new), sum);
+        m_run[ht] = m_new;
       }
-      float tmax = s[0][0];
-#pragma unroll
-      for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[rb][r]);
-      const float m_new = fmaxf(m_run, tmax * sc);  // sc > 0
-      float sum = 0.f;
-#pragma unroll
-      for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(fmaf(s[rb][r], sc, -m_new));
-      // every tile holds at least one real key for this half of the lanes? not necessarily (ragged tail with
-      // fewer than 5 keys): then tmax = -inf, m_new = m_run, sum = 0 and nothing changes
-      l_run = (m_new == -INFINITY) ? 0.f : fmaf(l_run, __builtin_amdgcn_exp2f(m_run - m_new), sum);
-      m_run = m_new;
     } else {
       // ---- z - c per element, maxima by block relation of the query (row) to this lane's key
       const __attribute__((address_space(3))) f32x4* cq =
@@ -214,32 +227,42 @@ __global__ __launch_bounds__(kSseThreads, 2) void sse_pass_kernel(SseParams p) {
         for (int q4 = 0; q4 < 4; ++q4) {
           const f32x4 cv = cq[(32 * rb + 8 * q4 + 4 * g) >> 2];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) s[rb][4 * q4 + e] = fmaf(s[rb][4 * q4 + e], sc, -cv[e]);
+          for (int ht = 0; ht < HT; ++ht)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) s[ht][rb][4 * q4 + e] = fmaf(s[ht][rb][4 * q4 + e], sc, -cv[e]);
         }
       const int row1 = row0 + kSseTile;  // one past the tile's last query
-      const bool all_up = row1 <= w_lo_min && row1 <= L;     // every query sits in an earlier block than every key
-      const bool all_low = row0 >= w_hi_max;                 // ... in a later block
+      const bool all_up = row1 <= w_lo_min;                            // every query in an earlier block than every key
+      const bool all_low = row0 >= w_hi_max && row1 <= L;              // ... in a later block
       const bool all_diag = row0 >= w_lo_max && row1 <= w_hi_min && row1 <= L;
-      if (all_up || all_diag || (all_low && row1 <= L)) {    // wave-uniform
-        float tmax = s[0][0];
+      if (all_up || all_diag || all_low) {  // wave-uniform
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
+        for (int ht = 0; ht < HT; ++ht) {
+          float tmax = s[ht][0][0];
 #pragma unroll
-          for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[rb][r]);
-        if (all_up) mx_up = fmaxf(mx_up, tmax);
-        else if (all_diag) mx_diag = fmaxf(mx_diag, tmax);
-        else mx_low = fmaxf(mx_low, tmax);
+          for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[ht][rb][r]);
+          if (all_up) mx_up[ht] = fmaxf(mx_up[ht], tmax);
+          else if (all_diag) mx_diag[ht] = fmaxf(mx_diag[ht], tmax);
+          else mx_low[ht] = fmaxf(mx_low[ht], tmax);
+        }
       } else {  // a tile that straddles a block boundary of some key of this wave, or the ragged last tile
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
+        for (int ht = 0; ht < HT; ++ht) {
+          const int my_row = held0 + 32 * ht + c;
+          const int my_lo = (my_row / L_B) * L_B, my_hi = my_lo + L_B;
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int i = row0 + 32 * rb + 8 * (r >> 2) + 4 * g + (r & 3);
-            const float v = i < L ? s[rb][r] : -INFINITY;
-            if (i < my_lo) mx_up = fmaxf(mx_up, v);
-            else if (i < my_hi) mx_diag = fmaxf(mx_diag, v);
-            else mx_low = fmaxf(mx_low, v);
-          }
+          for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int i = row0 + 32 * rb + 8 * (r >> 2) + 4 * g + (r & 3);
+              const float v = i < L ? s[ht][rb][r] : -INFINITY;
+              mx_up[ht] = fmaxf(mx_up[ht], i < my_lo ? v : -INFINITY);
+              mx_diag[ht] = fmaxf(mx_diag[ht], (i >= my_lo && i < my_hi) ? v : -INFINITY);
+              mx_low[ht] = fmaxf(mx_low[ht], i >= my_hi ? v : -INFINITY);
+            }
+        }
       }
     }
     // tile t+1 must have landed before the next step; the loads of tiles t+2, t+3 may stay in flight
@@ -249,18 +272,22 @@ __global__ __launch_bounds__(kSseThreads, 2) void sse_pass_kernel(SseParams p) {
   wait_vmcnt<0>();  // nothing may still be writing this workgroup's LDS when it retires
 
   // ---- combine the two lane halves (they saw disjoint streamed rows) and store
-  if (!COLMAX) {
-    const float m_o = other_half(m_run, g), l_o = other_half(l_run, g);
-    const float m = fmaxf(m_run, m_o);
-    const float l = l_run * __builtin_amdgcn_exp2f(m_run - m) + l_o * __builtin_amdgcn_exp2f(m_o - m);
-    if (g == 0 && my_row < L) p.c[(long long)h * L + my_row] = m + __builtin_amdgcn_logf(l);  // v_log_f32 = log2
-  } else {
-    const float lo = half_swap_max(mx_low), di = half_swap_max(mx_diag), up = half_swap_max(mx_up);
-    if (g == 0 && my_row < L) {
-      float* o = p.part + (long long)h * 3 * L + my_row;
-      o[0] = __builtin_amdgcn_exp2f(lo);  // 2^-inf = 0: an empty query set
-      o[L] = __builtin_amdgcn_exp2f(di);
-      o[2 * (long long)L] = __builtin_amdgcn_exp2f(up);
+#pragma unroll
+  for (int ht = 0; ht < HT; ++ht) {
+    const int my_row = held0 + 32 * ht + c;
+    if (!COLMAX) {
+      const float m_o = other_half(m_run[ht], g), l_o = other_half(l_run[ht], g);
+      const float m = fmaxf(m_run[ht], m_o);
+      const float l = l_run[ht] * __builtin_amdgcn_exp2f(m_run[ht] - m) + l_o * __builtin_amdgcn_exp2f(m_o - m);
+      if (g == 0 && my_row < L) p.c[(long long)h * L + my_row] = m + __builtin_amdgcn_logf(l);  // v_log_f32 = log2
+    } else {
+      const float lo = half_swap_max(mx_low[ht]), di = half_swap_max(mx_diag[ht]), up = half_swap_max(mx_up[ht]);
+      if (g == 0 && my_row < L) {
+        float* o = p.part + (long long)h * 3 * L + my_row;
+        o[0] = __builtin_amdgcn_exp2f(lo);  // 2^-inf = 0: an empty query set
+        o[L] = __builtin_amdgcn_exp2f(di);
+        o[2 * (long long)L] = __builtin_amdgcn_exp2f(up);
+      }
     }
   }
 }
@@ -288,15 +315,19 @@ __global__ void sse_combine_kernel(const float* __restrict__ part, int L, int N,
 
 template <int D, bool COLMAX>
 int launch_pass(hipStream_t st, const SseParams& p) {
+  // One 32-row group per wave and two workgroups per CU.  Two groups per wave (half the LDS reads per matrix
+  // instruction, one workgroup per CU) measured the same: LDS read bandwidth is not what bounds the passes.
+  constexpr int HT = 1;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(sse_pass_kernel<D, COLMAX>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(sse_pass_kernel<D, COLMAX, HT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, sse_lds_bytes(D));
     if (e != hipSuccess) return record_hip_error(e);
     attr_set = true;
   }
-  const int grid = ((p.L + kSseHeld - 1) / kSseHeld) * p.N;
-  hipLaunchKernelGGL((sse_pass_kernel<D, COLMAX>), dim3(grid), dim3(kSseThreads), sse_lds_bytes(D), st, p);
+  constexpr int HELD = kSseWaves * 32 * HT;
+  const int grid = ((p.L + HELD - 1) / HELD) * p.N;
+  hipLaunchKernelGGL((sse_pass_kernel<D, COLMAX, HT>), dim3(grid), dim3(kSseThreads), sse_lds_bytes(D), st, p);
   return check_launch();
 }
 
