@@ -364,8 +364,30 @@ int pafu_step_layers(void* stream, const pafu_step_args* args, int n_layers) {
     int rc = check_step(&args[l]);
     if (rc) return rc;
   }
+  // The layers are independent, so the order of their stages is free: all scores first, then every layer's selection
+  // in one launch (a selection occupies a single CU; one per layer in a row would leave the chip idle 30 times), then
+  // compaction and attention layer by layer.
+  hipStream_t st = static_cast<hipStream_t>(stream);
   for (int l = 0; l < n_layers; ++l) {
-    int rc = enqueue_step(static_cast<hipStream_t>(stream), &args[l]);
+    int rc = enqueue_scores(st, &args[l]);
+    if (rc) return rc;
+  }
+  for (int first = 0; first < n_layers; first += kSelectBatchMax) {
+    SelectJob jobs[kSelectBatchMax];
+    int m = 0;
+    for (int l = first; l < n_layers && l < first + kSelectBatchMax; ++l) {
+      const pafu_step_args* a = &args[l];
+      if (a->n <= 0) continue;
+      jobs[m++] = SelectJob{a->mode == PAFU_MODE_SINGLE ? a->scores : a->SL_in, a->ids, nullptr, a->n, a->k, a->n_pinned};
+    }
+    if (m > 0) {
+      int rc = launch_select_batch(st, jobs, m);
+      if (rc) return rc;
+    }
+  }
+  for (int l = 0; l < n_layers; ++l) {
+    const pafu_step_args* a = &args[l];
+    int rc = enqueue_kv(st, a, a->ids, a->mode == PAFU_MODE_SINGLE ? a->scores : a->SL_in, a->SL_out);
     if (rc) return rc;
   }
   return PAFU_OK;

@@ -28,6 +28,18 @@ int launch_compact(hipStream_t st, const void* K, const void* V, const float* SL
                    long long ld_out_bytes);
 int launch_append(hipStream_t st, const void* K, const void* V, const float* S, long long ld_in_bytes, int rows,
                   int row_bytes, void* K_out, void* V_out, float* S_out, long long ld_out_bytes);
+// One top-k selection: scores [n] -> the min(k, n) retained indices, ascending (out_count may be null).
+struct SelectJob {
+  const float* scores;
+  int* out_ids;
+  int* out_count;
+  int n;
+  int k;
+  int n_pinned;  // tokens [0, n_pinned) rank above every score
+};
+constexpr int kSelectBatchMax = 32;  // lists per launch (the jobs travel as kernel arguments)
+// Independent lists, one workgroup each, in as few launches as possible.
+int launch_select_batch(hipStream_t st, const SelectJob* jobs, int count);
 int launch_select(hipStream_t st, const float* scores, int n, int k, int n_pinned, int* out_ids, int* out_count,
                   void* ws);
 int launch_score(hipStream_t st, const void* x0, const void* x1, const void* x2, int n_seg, int T, int Fs,

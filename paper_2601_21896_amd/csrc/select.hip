@@ -21,14 +21,7 @@ constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kSelTile = kSelThreads * 4;
 
-struct SelectProblem {
-  const float* scores;
-  int* out_ids;
-  int* out_count;
-  int n;
-  int k;
-  int n_pinned;  // tokens [0, n_pinned) rank above every score
-};
+typedef SelectJob SelectProblem;  // {scores, out_ids, out_count, n, k, n_pinned}
 
 // fp32 -> uint32 such that key order == (score order with -0 == +0 and NaN lowest).
 __device__ __forceinline__ uint32_t score_key(float f) {
@@ -44,7 +37,7 @@ __device__ __forceinline__ uint32_t token_key(float f, int i, int n_pinned) {
   return i < n_pinned ? 0xffffffffu : score_key(f);
 }
 
-__global__ __launch_bounds__(kSelThreads) void select_topk_kernel(SelectProblem P) {
+__device__ __forceinline__ void select_topk_body(const SelectProblem& P) {
   __shared__ uint32_t hist[kSelWaves][256];
   __shared__ uint32_t wave_tot[kSelWaves];
   __shared__ uint32_t s_prefix, s_remaining;
@@ -195,7 +188,7 @@ __device__ __forceinline__ void transpose32(uint32_t (&a)[32]) {
 // W = 32-key words per thread, NT threads: the list holds at most NT * 32 * W scores.  Longer lists use fewer
 // threads so that the W * 32 bit-plane registers fit.
 template <int W, int NT>
-__global__ __launch_bounds__(NT) void select_bitslice_kernel(SelectProblem P) {
+__device__ __forceinline__ void select_bitslice_body(const SelectProblem& P) {
   constexpr int kWaves = NT / 64;
   __shared__ int part[2][kWaves];
   __shared__ uint32_t wave_tot[kWaves];
@@ -303,7 +296,41 @@ __global__ __launch_bounds__(NT) void select_bitslice_kernel(SelectProblem P) {
   if (tid == 0 && P.out_count) *P.out_count = P.k;
 }
 
+// One score list per workgroup: the single-list entry points launch one workgroup, the multi-layer steps one per
+// layer (the lists are independent, and a list only ever occupies one CU).
+struct SelectBatch {
+  SelectProblem job[kSelectBatchMax];
+};
+template <int W, int NT>
+__global__ __launch_bounds__(NT) void select_bitslice_kernel(SelectBatch B) {
+  select_bitslice_body<W, NT>(B.job[blockIdx.x]);
+}
+__global__ __launch_bounds__(kSelThreads) void select_topk_kernel(SelectBatch B) { select_topk_body(B.job[blockIdx.x]); }
+
 }  // namespace
+
+int launch_select_batch(hipStream_t st, const SelectJob* jobs, int count) {
+  for (int first = 0; first < count; first += kSelectBatchMax) {
+    const int m = count - first < kSelectBatchMax ? count - first : kSelectBatchMax;
+    SelectBatch B;
+    int n_max = 0;
+    for (int i = 0; i < m; ++i) {
+      B.job[i] = jobs[first + i];
+      if (B.job[i].n < 0) B.job[i].n = 0;
+      if (B.job[i].n_pinned < 0) B.job[i].n_pinned = 0;
+      n_max = B.job[i].n > n_max ? B.job[i].n : n_max;
+    }
+    for (int i = m; i < kSelectBatchMax; ++i) B.job[i] = B.job[0];  // never read: the grid has m workgroups
+    // the longest list picks the kernel (keys per thread x threads must cover it)
+    if (n_max <= 256 * 32) hipLaunchKernelGGL((select_bitslice_kernel<1, 256>), dim3(m), dim3(256), 0, st, B);
+    else if (n_max <= 512 * 32 * 2) hipLaunchKernelGGL((select_bitslice_kernel<2, 512>), dim3(m), dim3(512), 0, st, B);
+    else if (n_max <= 1024 * 32 * 2) hipLaunchKernelGGL((select_bitslice_kernel<2, 1024>), dim3(m), dim3(1024), 0, st, B);
+    else hipLaunchKernelGGL(select_topk_kernel, dim3(m), dim3(kSelThreads), 0, st, B);
+    int rc = check_launch();
+    if (rc) return rc;
+  }
+  return PAFU_OK;
+}
 
 int launch_select(hipStream_t st, const float* scores, int n, int k, int n_pinned, int* out_ids, int* out_count,
                   void* ws) {
@@ -311,12 +338,8 @@ int launch_select(hipStream_t st, const float* scores, int n, int k, int n_pinne
   if (n <= 0 || k <= 0) {
     if (out_count == nullptr) return PAFU_OK;
   }
-  SelectProblem P{scores, out_ids, out_count, n < 0 ? 0 : n, k, n_pinned < 0 ? 0 : n_pinned};
-  if (P.n <= 256 * 32) hipLaunchKernelGGL((select_bitslice_kernel<1, 256>), dim3(1), dim3(256), 0, st, P);
-  else if (P.n <= 512 * 32 * 2) hipLaunchKernelGGL((select_bitslice_kernel<2, 512>), dim3(1), dim3(512), 0, st, P);
-  else if (P.n <= 1024 * 32 * 2) hipLaunchKernelGGL((select_bitslice_kernel<2, 1024>), dim3(1), dim3(1024), 0, st, P);
-  else hipLaunchKernelGGL(select_topk_kernel, dim3(1), dim3(kSelThreads), 0, st, P);
-  return check_launch();
+  const SelectJob job{scores, out_ids, out_count, n, k, n_pinned};
+  return launch_select_batch(st, &job, 1);
 }
 
 }  // namespace pafu

@@ -119,6 +119,20 @@ def test_step_layers_independent():
     assert ids_seen[0] != ids_seen[1]
 
 
+def test_step_layers_many_layers_with_different_cache_sizes():
+    # more layers than one batched selection launch holds, cache sizes differ from layer to layer (one is empty)
+    packs, metas = [], []
+    for l in range(34):
+        frames = [0, 2, 5, 3][l % 4]
+        cfg = wl.scaled(wl.C1, frame_tokens=16, cache_frames=frames, chunk_frames=1, k=40)
+        d = wl.make_layer_inputs(cfg, seed=wl.BASE_SEED + 11 + 1000 * l)
+        packs.append(_single(cfg, d, 40, cfg.Lc))
+        metas.append((cfg, d))
+    B.pafu_step_layers([p[0] for p in packs])
+    for (cfg, d), p in zip(metas, packs):
+        _check_single(cfg, d, 40, cfg.Lc, p)
+
+
 def _rollout(cfg, k, n_chunks, L_B, stop_at=None, resume=None, n_pinned=0):
     """Runs the device rollout beside the oracle's (teacher-forced on the chunk scores)."""
     N, D, Lc = cfg.N, cfg.D, cfg.Lc
