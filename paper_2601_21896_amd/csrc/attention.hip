@@ -453,7 +453,7 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnPara
       issue_tiles(t + kAtStages);
       if ((t + 1) * kAtTileKeys > lim_min) attn_mask(s_a, t * kAtTileKeys, lim, g);
       attn_step<D>(s_a, s_b, p_b, p_a, o, qf, msc, l_run, k_addr(t + 1), v_addr(t > 0 ? t - 1 : 0), kx2, vx2, sc);
-      wait_vmcnt<2 * (2 * LPT + (GATHER ? 1 : 0))>();
+      wait_vmcnt<(kAtStages - 2) * (2 * LPT + (GATHER ? 1 : 0))>();
       __builtin_amdgcn_s_barrier();
     }
     {
@@ -462,7 +462,7 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnPara
       issue_tiles(t + kAtStages);
       if ((t + 1) * kAtTileKeys > lim_min) attn_mask(s_b, t * kAtTileKeys, lim, g);
       attn_step<D>(s_b, s_a, p_a, p_b, o, qf, msc, l_run, k_addr(T + 1 < n_iter ? t + 1 : t), v_addr(t - 1), kx2, vx2, sc);
-      wait_vmcnt<2 * (2 * LPT + (GATHER ? 1 : 0))>();
+      wait_vmcnt<(kAtStages - 2) * (2 * LPT + (GATHER ? 1 : 0))>();
       __builtin_amdgcn_s_barrier();
     }
   }
