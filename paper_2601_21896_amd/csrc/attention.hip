@@ -439,6 +439,20 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnPara
     }
   }
 
+  // A wave whose 32 queries all lie past the end (the last query tile of a head is usually ragged) still loads its
+  // share of every tile and joins every barrier, but does no arithmetic: on this chip energy is time.
+  if (__builtin_amdgcn_readfirstlane(i_first + wave * 32) >= p.Lq) {
+#pragma unroll 1
+    for (int t = 0; t < 2 * n_iter; ++t) {
+      if (GATHER) issue_ids(t + kAtStages + kAtIdLead);
+      issue_tiles(t + kAtStages);
+      wait_vmcnt<(kAtStages - 2) * (2 * LPT + (GATHER ? 1 : 0))>();
+      __builtin_amdgcn_s_barrier();
+    }
+    wait_vmcnt<0>();
+    return;
+  }
+
   // Step t: S^T(t+1) into the "next" registers, softmax of S^T(t), O^T += tile t-1.  Iteration T runs step 2T
   // (s_a -> p_a, next into s_b, adds p_b) and step 2T+1 (s_b -> p_b, next into s_a, adds p_a).  The tile count is
   // padded to even: a tile past the end is fully masked and contributes nothing.  Before the first tile p_b is
