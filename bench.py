@@ -325,9 +325,12 @@ def main():
     # the timed whole steps is the step time minus the three short stages.  It is a few percent longer than the
     # duration between the stage events above, where the event records leave the chip short rests; the roofline
     # figure uses the in-step duration, which is also what the rocprofv3 average over the same command shows.
-    # (a multi-layer step selects for up to 32 layers in one launch, one workgroup per layer)
-    select_share = avg["select"] * ((n_layers + 31) // 32) / n_layers
-    attn_in_step_ms = ms_per_step / n_layers - (avg["score"] + select_share + avg["compact"])
+    # (a multi-layer step selects for up to 32 layers in one launch, one workgroup per layer; with shared indices it
+    # scores and selects once for all layers).  Never report less than the duration between the stage events.
+    shared = a.shared_index and n_layers > 1
+    score_share = avg["score"] / n_layers if shared else avg["score"]
+    select_share = avg["select"] / n_layers if shared else avg["select"] * ((n_layers + 31) // 32) / n_layers
+    attn_in_step_ms = max(ms_per_step / n_layers - (score_share + select_share + avg["compact"]), avg["attention"])
     attn_in_step_tflops = attn_flops / (attn_in_step_ms * 1e-3) / 1e12
     roofline = {"kernel": "chunk_attention_kernel", "bound": "mfma", "achieved": attn_in_step_tflops,
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": attn_in_step_tflops / PEAK_BF16_TFLOPS,
