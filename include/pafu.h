@@ -64,8 +64,8 @@ int pafu_version(void);
  *   W2       : [n_out, M] fp32 row-major;  b2 : [n_out] fp32 or NULL
  *   out      : [T] fp32
  *   workspace: pafu_score_workspace_bytes(M) bytes (holds the output-averaged second layer)
- * bf16 inputs with F % 64 == 0 and M % 32 == 0 take the MFMA path (fp32 accumulate); anything
- * else takes a plain fp32-FMA path.  T == 0 is a no-op.
+ * bf16 inputs with Fs % 64 == 0 and M % 32 == 0 take the MFMA paths (fp32 accumulate; M % 256 == 0 the
+ * streaming kernel); anything else takes a plain fp32-FMA path.  T == 0 is a no-op.
  */
 size_t pafu_score_workspace_bytes(int M);
 int pafu_score(void* stream, const void* x0, const void* x1, const void* x2, int n_seg, int T, int Fs,
