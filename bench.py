@@ -137,7 +137,7 @@ def rollout(a, torch, np, B, wl):
     flops = 4.0 * Lc * (n_kept + Lc) * D * N
     peak_cache = 2 * (cap * N * D * 2 * 2 + cap * 4)
     out = {
-        "metric": "ms per AR chunk step (score+select+compact+attn)", "value": float(np.median(steady)), "unit": "ms",
+        "metric": "ms per AR chunk step (score+select+compact+attn), MFMA util and HBM GB/s", "value": float(np.median(steady)), "unit": "ms",
         "n_gpus": 1, "steps": len(steady), "warmup": n_chunks + 5, "ms_per_step": float(np.median(steady)),
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "C3: %d-chunk rollout, 12 heads x 128, chunk %d queries, budget %d tokens, steady cache "
@@ -369,7 +369,7 @@ def main():
                              "attention_extrapolated": attn_full_ms}}
 
     out = {
-        "metric": "ms per AR chunk step (score+select+compact+attn)",
+        "metric": "ms per AR chunk step (score+select+compact+attn), MFMA util and HBM GB/s",
         "value": ms_per_step, "unit": "ms", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
