@@ -268,6 +268,7 @@ __global__ __launch_bounds__(512, 1) void score_stream_kernel(
   constexpr int LX = (XU + 7) / 8;                     // feature loads per wave per slab
   constexpr int LPW = LW + LX;
   constexpr int KS = kS3Slab / 32;                     // k-steps (16 features) per wave per slab
+  static_assert(KS % 2 == 0, "the two fragment sets alternate per k-step and must line up across slabs");
   typedef __attribute__((address_space(3))) unsigned char lds_byte;
   typedef __attribute__((address_space(3))) bf16x8 lds_frag;
   typedef float f32x4_t __attribute__((ext_vector_type(4)));
@@ -336,28 +337,63 @@ __global__ __launch_bounds__(512, 1) void score_stream_kernel(
                                                    st_ + kS3WBytes + ((wave + 8 * j) % XU) * 1024)));           \
   } while (0)
 
+    // Fragments of k-step j of a slab: two W1 blocks and TT feature tiles, into fragment set B (0 or 1).
+#define PAFU_S3_READ(B, ST, J)                                                                                  \
+  do {                                                                                                          \
+    fw[B][0] = *(const lds_frag*)((ST) + (hq * 64) * kS3RowB + rd[J]);                                          \
+    fw[B][1] = *(const lds_frag*)((ST) + (hq * 64 + 32) * kS3RowB + rd[J]);                                     \
+    _Pragma("unroll") for (int tt = 0; tt < TT; ++tt)                                                           \
+        fx[B][tt] = *(const lds_frag*)((ST) + kS3WBytes + tt * 32 * kS3RowB + rd[J]);                           \
+  } while (0)
+#define PAFU_S3_MMA(B)                                                                                          \
+  do {                                                                                                          \
+    _Pragma("unroll") for (int tt = 0; tt < TT; ++tt) {                                                         \
+      acc[tt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[B][0], fx[B][tt], acc[tt][0], 0, 0, 0);           \
+      acc[tt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[B][1], fx[B][tt], acc[tt][1], 0, 0, 0);           \
+    }                                                                                                           \
+  } while (0)
+
+    // Software pipeline.  The fragments of the next k-step are read while the matrix instructions of the current one
+    // run, also across slabs: the barrier sits before the LAST k-step of slab s, where every wave has its last
+    // fragments of slab s in registers (so the slab's stage can be refilled) and where slab s+1 must have landed (so
+    // its first fragments can be fetched under the last k-step of slab s).  Ring: stage of slab s being refilled
+    // with slab s+3, slab s+1 ready, slab s+2 in flight.
+    bf16x8 fw[2][2], fx[2][TT];
+    const bool kh_first = __builtin_amdgcn_readfirstlane(kh) == 0;
     __syncthreads();  // every wave is done with the LDS contents of the previous pass
 #pragma unroll
-    for (int s = 0; s < kS3Stages - 1; ++s) PAFU_S3_ISSUE(s);
+    for (int s = 0; s < kS3Stages; ++s) PAFU_S3_ISSUE(s);
+    s3_wait_vmcnt<(kS3Stages - 1) * LPW>();
+    __builtin_amdgcn_s_barrier();  // slab 0 visible to all
+    PAFU_S3_READ(0, ring, 0);
 #pragma unroll 1
     for (int s = 0; s < n_slabs; ++s) {
-      // slab s was issued kS3Stages - 1 iterations ago: only the loads of the younger slabs may still be in flight
-      s3_wait_vmcnt<(kS3Stages - 2) * LPW>();
-      __builtin_amdgcn_s_barrier();  // slab s visible to all; everyone is done reading slab s-1
-      PAFU_S3_ISSUE(s + kS3Stages - 1);  // into the stage slab s-1 just vacated
       const lds_byte* st = ring + (s % kS3Stages) * kStageB;
+      const lds_byte* st_next = ring + ((s + 1) % kS3Stages) * kStageB;
 #pragma unroll
       for (int j = 0; j < KS; ++j) {
-        const bf16x8 a0 = *(const lds_frag*)(st + (hq * 64) * kS3RowB + rd[j]);
-        const bf16x8 a1 = *(const lds_frag*)(st + (hq * 64 + 32) * kS3RowB + rd[j]);
-#pragma unroll
-        for (int tt = 0; tt < TT; ++tt) {
-          const bf16x8 xf = *(const lds_frag*)(st + kS3WBytes + tt * 32 * kS3RowB + rd[j]);
-          acc[tt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, xf, acc[tt][0], 0, 0, 0);
-          acc[tt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, xf, acc[tt][1], 0, 0, 0);
+        if (j + 1 < KS) {
+          PAFU_S3_READ((j + 1) & 1, st, j + 1);
+        } else {
+          // own fragment reads of slab s complete (they must be before the stage is handed back), then the loads
+          // of slab s+1 (issued two barriers ago; only the slab after it may still be in flight)
+          __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0), other counters left alone
+          s3_wait_vmcnt<(kS3Stages - 2) * LPW>();
+          __builtin_amdgcn_s_barrier();
+          // refill the stage of slab s.  A wave cannot issue anything else while its loads queue up behind a busy
+          // memory pipe, so the two waves of a SIMD (kh = 0, 1) take turns: one issues its loads before this
+          // k-step's matrix instructions, the other after them.
+          if (kh_first) PAFU_S3_ISSUE(s + kS3Stages);
+          PAFU_S3_READ((j + 1) & 1, st_next, 0);
         }
+        __builtin_amdgcn_sched_barrier(0);
+        PAFU_S3_MMA(j & 1);
+        __builtin_amdgcn_sched_barrier(0);
+        if (j + 1 == KS && !kh_first) PAFU_S3_ISSUE(s + kS3Stages);
       }
     }
+#undef PAFU_S3_READ
+#undef PAFU_S3_MMA
 #undef PAFU_S3_ISSUE
     // ---- add the two halves of the reduction axis: wave (hq, 1) hands its accumulators to wave (hq, 0) through LDS,
     // one token tile at a time, alternating between two 32 KB regions so that one barrier per tile is enough.
