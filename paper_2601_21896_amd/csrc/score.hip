@@ -275,7 +275,8 @@ __global__ __launch_bounds__(512, 1) void score_stream_kernel(
   typedef __attribute__((address_space(3))) f32x4_t lds_f4;
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds_raw[];
   lds_byte* const ring = (lds_byte*)lds_raw;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // said to be uniform: LDS addresses of the loads stay scalar
   const int hq = wave & 3, kh = wave >> 2;
   const int g = lane >> 5, c = lane & 31;
   const int tok_base = blockIdx.x * (32 * TT);
@@ -328,13 +329,13 @@ __global__ __launch_bounds__(512, 1) void score_stream_kernel(
     lds_byte* st_ = ring + (s_ % kS3Stages) * kStageB;                                                          \
     _Pragma("unroll") for (int j = 0; j < LW; ++j)                                                              \
         s3_dma(w_pass + sc_ * kS3Slab, w_off[j],                                                                \
-               __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(st_ + (wave + 8 * j) * 1024)));             \
+               (unsigned)(uintptr_t)(st_ + (wave + 8 * j) * 1024));                                             \
     const int seg_ = sc_ / slabs_per_seg;                                                                       \
     const int fo_ = (sc_ - seg_ * slabs_per_seg) * kS3Slab;                                                     \
     const unsigned short* xs_ = seg_ == 0 ? x0 : (seg_ == 1 ? x1 : x2);                                         \
     _Pragma("unroll") for (int j = 0; j < LX; ++j)                                                              \
-        s3_dma(xs_ + x_wg_off + fo_, x_off[j], __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(            \
-                                                   st_ + kS3WBytes + ((wave + 8 * j) % XU) * 1024)));           \
+        s3_dma(xs_ + x_wg_off + fo_, x_off[j],                                                                  \
+               (unsigned)(uintptr_t)(st_ + kS3WBytes + ((wave + 8 * j) % XU) * 1024));                          \
   } while (0)
 
     // Fragments of k-step j of a slab: two W1 blocks and TT feature tiles, into fragment set B (0 or 1).
@@ -359,7 +360,7 @@ __global__ __launch_bounds__(512, 1) void score_stream_kernel(
     // its first fragments can be fetched under the last k-step of slab s).  Ring: stage of slab s being refilled
     // with slab s+3, slab s+1 ready, slab s+2 in flight.
     bf16x8 fw[2][2], fx[2][TT];
-    const bool kh_first = __builtin_amdgcn_readfirstlane(kh) == 0;
+    const bool kh_first = kh == 0;
     __syncthreads();  // every wave is done with the LDS contents of the previous pass
 #pragma unroll
     for (int s = 0; s < kS3Stages; ++s) PAFU_S3_ISSUE(s);
