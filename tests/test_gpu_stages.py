@@ -79,7 +79,9 @@ def _run_select(s_np, k):
     return out[:m].cpu().numpy()
 
 
-@pytest.mark.parametrize("n", [1, 2, 63, 64, 255, 1000, 4095, 4096, 4097, 9001, 32760, 75600])
+# sizes on both sides of every kernel choice: 1 x 256, 2 x 512, 2 x 1024, 3 x 1024 words x threads, then the fallback
+@pytest.mark.parametrize("n", [1, 2, 63, 64, 255, 1000, 4095, 4096, 4097, 8192, 8193, 9001, 32760, 32768, 32769, 65536,
+                               65537, 75600, 98304, 98305, 120000])
 def test_select_matches_oracle_with_ties(n):
     rng = np.random.default_rng(n)
     coarse = (rng.integers(-4, 5, size=n) * 0.25).astype(np.float32)     # many ties at the threshold
