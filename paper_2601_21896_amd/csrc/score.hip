@@ -396,57 +396,69 @@ __global__ __launch_bounds__(512, 1) void score_stream_kernel(
 #undef PAFU_S3_READ
 #undef PAFU_S3_MMA
 #undef PAFU_S3_ISSUE
-    // ---- add the two halves of the reduction axis: wave (hq, 1) hands its accumulators to wave (hq, 0) through LDS,
-    // one token tile at a time, alternating between two 32 KB regions so that one barrier per tile is enough.
+    // ---- add the two halves of the reduction axis through LDS, one token tile at a time, alternating between two
+    // 32 KB regions so that one barrier per tile is enough.  The two waves (hq, 0) and (hq, 1) swap one 32-unit block
+    // each: wave kh ends up with the complete sums of block b = kh and applies bias, activation and second layer
+    // to it, so that both waves of a SIMD share that work.
     s3_wait_vmcnt<0>();
     __syncthreads();  // all loads have landed and all fragment reads are done: the ring can be reused
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
-      lds_f4* reg = (lds_f4*)(ring + (tt & 1) * 32768) + hq * 8 * 64 + lane;
-      if (kh == 1) {
+      lds_f4* reg = (lds_f4*)(ring + (tt & 1) * 32768) + (hq * 2 + kh) * 4 * 64 + lane;       // what this wave sends
+      const lds_f4* got = (const lds_f4*)(ring + (tt & 1) * 32768) + (hq * 2 + (kh ^ 1)) * 4 * 64 + lane;
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-          for (int q = 0; q < 4; ++q)
-            reg[(b * 4 + q) * 64] =
-                f32x4_t{acc[tt][b][4 * q], acc[tt][b][4 * q + 1], acc[tt][b][4 * q + 2], acc[tt][b][4 * q + 3]};
+      for (int q = 0; q < 4; ++q) {
+        if (kh == 0) reg[q * 64] = f32x4_t{acc[tt][1][4 * q], acc[tt][1][4 * q + 1], acc[tt][1][4 * q + 2], acc[tt][1][4 * q + 3]};
+        else reg[q * 64] = f32x4_t{acc[tt][0][4 * q], acc[tt][0][4 * q + 1], acc[tt][0][4 * q + 2], acc[tt][0][4 * q + 3]};
       }
       __syncthreads();
-      if (kh == 0) {
-        // activation and second layer; the lane holds token c of tile tt and hidden units
-        // mp + 64 hq + 32 b + 8 q + 4 g + e
+      // the lane holds token c of tile tt and hidden units mp + 64 hq + 32 kh + 8 q + 4 g + e
+      float hsum[16];
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+      for (int q = 0; q < 4; ++q) {
+        const f32x4_t o = got[q * 64];
+        const int m0 = mp + 64 * hq + 32 * kh + 8 * q + 4 * g;
+        float4 bb = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (b1 != nullptr) bb = *reinterpret_cast<const float4*>(b1 + m0);
+        const float ov[4] = {o.x, o.y, o.z, o.w}, bv[4] = {bb.x, bb.y, bb.z, bb.w};
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const f32x4_t o = reg[(b * 4 + q) * 64];
-            const int m0 = mp + 64 * hq + 32 * b + 8 * q + 4 * g;
-            const float4 w = *reinterpret_cast<const float4*>(w2bar + m0);
-            float4 bb = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (b1 != nullptr) bb = *reinterpret_cast<const float4*>(b1 + m0);
-            const float ov[4] = {o.x, o.y, o.z, o.w}, wv[4] = {w.x, w.y, w.z, w.w}, bv[4] = {bb.x, bb.y, bb.z, bb.w};
+        for (int e = 0; e < 4; ++e)
+          hsum[4 * q + e] = (kh == 0 ? acc[tt][0][4 * q + e] : acc[tt][1][4 * q + e]) + ov[e] + bv[e];
+      }
+      if (act == PAFU_ACT_SILU) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const float h = acc[tt][b][4 * q + e] + ov[e] + bv[e];
-              partial[tt] = fmaf(wv[e], act == PAFU_ACT_SILU ? fast_silu(h) : act_accurate(h, act), partial[tt]);
-            }
-          }
+        for (int i = 0; i < 16; ++i) hsum[i] = fast_silu(hsum[i]);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) hsum[i] = act_accurate(hsum[i], act);
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float4 w = *reinterpret_cast<const float4*>(w2bar + mp + 64 * hq + 32 * kh + 8 * q + 4 * g);
+        partial[tt] = fmaf(w.x, hsum[4 * q], partial[tt]);
+        partial[tt] = fmaf(w.y, hsum[4 * q + 1], partial[tt]);
+        partial[tt] = fmaf(w.z, hsum[4 * q + 2], partial[tt]);
+        partial[tt] = fmaf(w.w, hsum[4 * q + 3], partial[tt]);
       }
     }
   }
-  // ---- add the two lane halves, then the four hidden quarters
+  // ---- add the two lane halves, then the eight waves (each holds the part of its 32-unit blocks)
   __syncthreads();
   float* red = reinterpret_cast<float*>(lds_raw);
 #pragma unroll
   for (int tt = 0; tt < TT; ++tt) {
     partial[tt] += __shfl_xor(partial[tt], 32);
-    if (kh == 0 && g == 0) red[hq * (32 * TT) + tt * 32 + c] = partial[tt];
+    if (g == 0) red[wave * (32 * TT) + tt * 32 + c] = partial[tt];
   }
   __syncthreads();
   for (int i = tid; i < 32 * TT; i += 512) {
     const int tok = tok_base + i;
-    if (tok < T)
-      out[tok] = red[i] + red[32 * TT + i] + red[2 * 32 * TT + i] + red[3 * 32 * TT + i] + (b2bar ? *b2bar : 0.f);
+    if (tok < T) {
+      float v = b2bar ? *b2bar : 0.f;
+#pragma unroll
+      for (int w = 0; w < 8; ++w) v += red[w * (32 * TT) + i];
+      out[tok] = v;
+    }
   }
 }
 
