@@ -123,6 +123,19 @@ def test_select_special_values_and_degenerate_inputs():
     assert _run_select(np.zeros(0, np.float32), 3).shape == (0,)
 
 
+@pytest.mark.parametrize("n", [3000, 20000, 40000, 70000, 90000, 110000])
+def test_select_special_values_in_long_lists(n):
+    # every kernel variant sees NaN, infinities, signed zeros, denormals and heavy ties, also in its ragged last word
+    rng = np.random.default_rng(7 * n)
+    s = (rng.integers(-3, 4, size=n) * 0.5).astype(np.float32)
+    special = np.array([np.nan, -np.nan, np.inf, -np.inf, 0.0, -0.0, 1e-45, -1e-45, 3.4e38, -3.4e38], dtype=np.float32)
+    where = rng.choice(n, size=n // 7, replace=False)
+    s[where] = special[rng.integers(0, len(special), size=len(where))]
+    s[-5:] = [np.nan, -0.0, np.inf, 0.0, -np.inf]
+    for k in (1, n // 9, n // 2, n - 3):
+        assert np.array_equal(_run_select(s, k), orc.select_topk(s, k)), (n, k)
+
+
 def test_select_is_deterministic_across_runs():
     rng = np.random.default_rng(0)
     s = (rng.integers(0, 3, size=32760)).astype(np.float32)
