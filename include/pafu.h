@@ -14,7 +14,9 @@
  *    stride `ld_*` counted in ELEMENTS (so a slab with spare capacity works);
  *    inside a token the N*D elements are contiguous.  Scores are fp32, indices int32.
  *  - Device pointers must be 16-byte aligned and token strides multiples of 16 bytes.
- *  - Outputs must not alias inputs.  Weights and inputs are borrowed for the call.
+ *  - Outputs must not alias inputs or each other (PAFU_ERR_ALIAS).  Overlap is decided on the strided rows, so
+ *    tensors interleaved in one slab with a common stride (K and V side by side in a token) are fine.
+ *    Weights and inputs are borrowed for the call.
  *  - Return value: PAFU_OK (0) = enqueued; a negative pafu_status = error, in which
  *    case NOTHING was enqueued and no output is touched.
  *  - A budget k larger than the cache is not an error: everything is kept
@@ -211,7 +213,11 @@ typedef struct pafu_step_args {
 
 size_t pafu_step_workspace_bytes(const pafu_step_args* args /* host */);
 int pafu_step(void* stream, const pafu_step_args* args /* host */);
-/* The same step for n_layers independent layers (args[l] is layer l's arguments), enqueued on one stream. */
+/* The same step for n_layers independent layers (args[l] is layer l's arguments), enqueued on one stream.
+ * The layers' stages are NOT enqueued layer by layer: every layer is scored first, then all selections run in one
+ * launch (up to 32 score lists per launch), then compaction and attention follow layer by layer.  Every layer
+ * therefore needs its own scores, ids, SL_out, K_out, V_out and O buffers, and no layer's output may overlap
+ * another layer's input (PAFU_ERR_ALIAS); only the workspace may be shared between layers. */
 int pafu_step_layers(void* stream, const pafu_step_args* args /* host array */, int n_layers);
 
 /* pafu_step_layers_shared - the paper's own multi-layer arrangement (Sec. 3.3: the Salience Estimation Head sits on
@@ -222,7 +228,8 @@ int pafu_step_layers(void* stream, const pafu_step_args* args /* host array */, 
  * equal the index layer's - N, D, block_len, softmax_scale, out_dtype, ld_cache/ld_out/ld_chunk/ld_o, K_cache,
  * V_cache, Q, K_chunk, V_chunk, K_out, V_out, O); their feature, weight, score, ids and SL fields are ignored and
  * may be NULL.  The score list is compacted and extended for the index layer only.
- * Layers are enqueued in array order on one stream.
+ * The index layer's scoring and the selection are enqueued first, then the layers' caches in array order, on one
+ * stream; outputs of one layer must not overlap inputs or outputs of another (PAFU_ERR_ALIAS).
  */
 int pafu_step_layers_shared(void* stream, const pafu_step_args* args /* host array */, int n_layers,
                             int index_layer);

@@ -238,13 +238,17 @@ class RolloutState:
 
 
 def rollout_step(state: RolloutState, X_chunk, W1, b1, W2, b2, Q, K_chunk, V_chunk,
-                 k: int, block_len: int, act: str = "silu", forced_chunk_scores_f32=None, n_pinned: int = 0):
+                 k: int, block_len: int, act: str = "silu", forced_chunk_scores_f32=None, n_pinned: int = 0,
+                 rows=None):
     """One chunk of a rollout (Sec. 3.4 inference paragraph; Alg. 2).
 
     The chunk's scores join the stored ones after its step, so the next step's
     top-k runs over retained + that chunk and old and new tokens compete; stored
     scores are never refreshed.  Order: score the chunk; select on the stored SL;
     compact; attend over retained + chunk; append chunk K/V and its scores.
+
+    rows: optional query rows of the attention output to compute (full-size checks sample them; the
+    cache update does not depend on it).
 
     returns dict(s_chunk f64, ids, O); mutates state.
     """
@@ -253,7 +257,7 @@ def rollout_step(state: RolloutState, X_chunk, W1, b1, W2, b2, Q, K_chunk, V_chu
            else np.asarray(forced_chunk_scores_f32, np.float32))
     ids = select_topk(state.SL, k, n_pinned)
     Kk, Vk, SLk = compact_kv(state.K, state.V, state.SL, ids)
-    O = chunk_attention(Q, Kk, Vk, K_chunk, V_chunk, block_len)
+    O = chunk_attention(Q, Kk, Vk, K_chunk, V_chunk, block_len, rows=rows)
     state.K = np.concatenate([Kk, np.asarray(K_chunk, dtype=Kk.dtype)], axis=0)
     state.V = np.concatenate([Vk, np.asarray(V_chunk, dtype=Vk.dtype)], axis=0)
     state.SL = np.concatenate([SLk, s32]).astype(np.float32)
@@ -264,12 +268,12 @@ def rollout_step(state: RolloutState, X_chunk, W1, b1, W2, b2, Q, K_chunk, V_chu
 # Final-layer head, indices shared by all layers (Sec. 3.3)
 # --------------------------------------------------------------------------------------
 def step_single_shared(X_cache, X_chunk, W1, b1, W2, b2, layers, k: int, block_len: int, act: str = "silu",
-                       forced_scores_f32=None, n_pinned: int = 0):
+                       forced_scores_f32=None, n_pinned: int = 0, rows=None):
     """SINGLE-mode step of several layers with ONE index list (Sec. 3.3: the head reads the final layer only and
     its top-k indices update the caches of all layers).
 
     X_cache / X_chunk are the index layer's features; `layers` is a list of dicts with K_cache, V_cache, Q,
-    K_chunk, V_chunk (one per layer, same token counts).
+    K_chunk, V_chunk (one per layer, same token counts); rows: optional query rows of O to compute.
 
     returns dict(scores f64 [n+Lc], ids, SL_kept, layers=[dict(K_kept, V_kept, O)])
     """
@@ -283,7 +287,8 @@ def step_single_shared(X_cache, X_chunk, W1, b1, W2, b2, layers, k: int, block_l
     for L in layers:
         assert L["K_cache"].shape[0] == n
         Kk, Vk, _ = compact_kv(L["K_cache"], L["V_cache"], s32[:n], ids)
-        outs.append(dict(K_kept=Kk, V_kept=Vk, O=chunk_attention(L["Q"], Kk, Vk, L["K_chunk"], L["V_chunk"], block_len)))
+        outs.append(dict(K_kept=Kk, V_kept=Vk,
+                         O=chunk_attention(L["Q"], Kk, Vk, L["K_chunk"], L["V_chunk"], block_len, rows=rows)))
     return dict(scores=s, ids=ids, SL_kept=SLk, layers=outs)
 
 

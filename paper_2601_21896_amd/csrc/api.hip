@@ -65,7 +65,8 @@ int check_compact(const void* K, const void* V, const float* SL, long long ld_in
 int check_attention(const void* Q, int Lq, const void* Kc, const void* Vc, int n_kept, const void* Kn, const void* Vn,
                     int Lc, int N, int D, long long ld_q, long long ld_c, long long ld_n, long long ld_o,
                     int block_len, const void* O, int out_dtype) {
-  if (Lq < 1 || Lc < 1 || n_kept < 0 || N < 1 || N > 65535 || block_len < 1 || Lq > Lc) return PAFU_ERR_SHAPE;
+  if (Lq < 1 || Lc < 1 || n_kept < 0 || N < 1 || block_len < 1 || Lq > Lc) return PAFU_ERR_SHAPE;
+  if (((long long)Lq / 32 + 1) * N > 0x7fffffffll) return PAFU_ERR_SHAPE;  // one-dimensional grid
   if (D != 64 && D != 128) return PAFU_ERR_SHAPE;
   if ((long long)n_kept + Lc > 0x7fff0000ll) return PAFU_ERR_SHAPE;
   const int ob = dtype_bytes(out_dtype);
@@ -82,6 +83,102 @@ int check_attention(const void* Q, int Lq, const void* Kc, const void* Vc, int n
       (n_kept > 0 && (overlaps(O, o_bytes, Kc, (size_t)n_kept * ld_c * 2) ||
                       overlaps(O, o_bytes, Vc, (size_t)n_kept * ld_c * 2))))
     return PAFU_ERR_ALIAS;
+  return PAFU_OK;
+}
+
+// A strided buffer: `rows` rows of `row` bytes, `ld` bytes apart.
+struct Span {
+  const void* p;
+  long long rows, ld, row;
+};
+// Do two strided buffers share a byte?  Exact for equal strides (rows of one may sit in the gaps of the other, as
+// with K and V interleaved in one slab); otherwise decided on the enclosing byte ranges.
+bool spans_overlap(const Span& a, const Span& b) {
+  if (!a.p || !b.p || a.rows <= 0 || b.rows <= 0 || a.row <= 0 || b.row <= 0) return false;
+  const uintptr_t a0 = reinterpret_cast<uintptr_t>(a.p), b0 = reinterpret_cast<uintptr_t>(b.p);
+  const uintptr_t a1 = a0 + (uintptr_t)((a.rows - 1) * a.ld + a.row), b1 = b0 + (uintptr_t)((b.rows - 1) * b.ld + b.row);
+  if (a1 <= b0 || b1 <= a0) return false;
+  if (a.ld == b.ld && a.ld > 0) {
+    const uintptr_t ld = (uintptr_t)a.ld;
+    const uintptr_t delta = b0 >= a0 ? (b0 - a0) % ld : (ld - (a0 - b0) % ld) % ld;  // b's row start inside a's period
+    if (delta >= (uintptr_t)a.row && ld - delta >= (uintptr_t)b.row) return false;
+  }
+  return true;
+}
+
+// Everything a step reads and everything it writes (the workspace apart).  `scoring` is false for a layer that takes
+// its indices from another layer: then only the cache part counts.
+struct StepSpans {
+  Span in[20], out[8];
+  int n_in = 0, n_out = 0;
+};
+void step_spans(const pafu_step_args* a, bool scoring, StepSpans& s) {
+  const long long n = a->n, Lc = a->Lc, n_kept = a->k < a->n ? a->k : a->n;
+  const bool single = a->mode == PAFU_MODE_SINGLE;
+  const long long rowb = (long long)a->N * a->D * 2;
+  const long long out_rows = n_kept + (single ? 0 : Lc);
+  auto in = [&](const void* p, long long rows, long long ld, long long row) { s.in[s.n_in++] = Span{p, rows, ld, row}; };
+  auto out = [&](const void* p, long long rows, long long ld, long long row) { s.out[s.n_out++] = Span{p, rows, ld, row}; };
+  if (scoring) {
+    const long long eb = dtype_bytes(a->x_dtype), F = (long long)a->n_seg * a->Fs;
+    for (int g = 0; g < a->n_seg && g < 3; ++g) {
+      if (single) in(a->x_cache[g], n, a->ld_x * eb, a->Fs * eb);
+      in(a->x_chunk[g], Lc, a->ld_x * eb, a->Fs * eb);
+    }
+    in(a->W1, 1, 0, (long long)a->M * F * eb);
+    in(a->b1, 1, 0, (long long)a->M * 4);
+    in(a->W2, 1, 0, (long long)a->n_out * a->M * 4);
+    in(a->b2, 1, 0, (long long)a->n_out * 4);
+    if (single) out(a->scores, 1, 0, (n + Lc) * 4);
+    else in(a->SL_in, 1, 0, n * 4);
+    out(a->ids, 1, 0, n_kept * 4);
+    out(a->SL_out, 1, 0, out_rows * 4);
+  }
+  in(a->K_cache, n, a->ld_cache * 2, rowb);
+  in(a->V_cache, n, a->ld_cache * 2, rowb);
+  in(a->Q, Lc, a->ld_chunk * 2, rowb);
+  in(a->K_chunk, Lc, a->ld_chunk * 2, rowb);
+  in(a->V_chunk, Lc, a->ld_chunk * 2, rowb);
+  out(a->K_out, out_rows, a->ld_out * 2, rowb);
+  out(a->V_out, out_rows, a->ld_out * 2, rowb);
+  out(a->O, Lc, a->ld_o * dtype_bytes(a->out_dtype), (long long)a->N * a->D * dtype_bytes(a->out_dtype));
+}
+// No output of a step may overlap one of its inputs, another output or the workspace (in ROLLOUT the output slab
+// counts with the appended chunk rows).
+int check_step_alias(const pafu_step_args* a, bool scoring) {
+  StepSpans s;
+  step_spans(a, scoring, s);
+  const Span ws{a->workspace, 1, 0, (long long)a->workspace_bytes};
+  for (int i = 0; i < s.n_out; ++i) {
+    for (int j = 0; j < s.n_in; ++j)
+      if (spans_overlap(s.out[i], s.in[j])) return PAFU_ERR_ALIAS;
+    for (int j = i + 1; j < s.n_out; ++j)
+      if (spans_overlap(s.out[i], s.out[j])) return PAFU_ERR_ALIAS;
+    if (scoring && spans_overlap(s.out[i], ws)) return PAFU_ERR_ALIAS;
+  }
+  if (scoring)
+    for (int j = 0; j < s.n_in; ++j)
+      if (spans_overlap(ws, s.in[j])) return PAFU_ERR_ALIAS;
+  return PAFU_OK;
+}
+// The multi-layer steps reorder the stages across layers (all scores, then all selections, then the caches), so what
+// one layer writes must not overlap what any other layer reads or writes.  Only the workspace may be shared.
+int check_layers_alias(const pafu_step_args* args, int n_layers, int index_layer /* -1: every layer scores */) {
+  for (int a = 0; a < n_layers; ++a) {
+    StepSpans sa;
+    step_spans(&args[a], index_layer < 0 || a == index_layer, sa);
+    for (int b = 0; b < n_layers; ++b) {
+      if (b == a) continue;
+      StepSpans sb;
+      step_spans(&args[b], index_layer < 0 || b == index_layer, sb);
+      for (int i = 0; i < sa.n_out; ++i) {
+        for (int j = 0; j < sb.n_in; ++j)
+          if (spans_overlap(sa.out[i], sb.in[j])) return PAFU_ERR_ALIAS;
+        for (int j = 0; b > a && j < sb.n_out; ++j)
+          if (spans_overlap(sa.out[i], sb.out[j])) return PAFU_ERR_ALIAS;
+      }
+    }
+  }
   return PAFU_OK;
 }
 
@@ -123,7 +220,7 @@ int check_step(const pafu_step_args* a) {
     if (!aligned16(a->K_out) || !aligned16(a->V_out) || (a->ld_out * 2) % 16 != 0) return PAFU_ERR_ALIGN;
     if (a->ld_out < (long long)a->N * a->D) return PAFU_ERR_SHAPE;
   }
-  return PAFU_OK;
+  return check_step_alias(a, true);
 }
 
 // The scoring part of a step: SINGLE scores cache + chunk into a->scores, ROLLOUT the chunk into SL_out behind the
@@ -213,7 +310,7 @@ int check_layer_kv(const pafu_step_args* a, const pafu_step_args* idx) {
     if (!aligned16(a->K_out) || !aligned16(a->V_out) || (a->ld_out * 2) % 16 != 0) return PAFU_ERR_ALIGN;
     if (a->ld_out < (long long)a->N * a->D) return PAFU_ERR_SHAPE;
   }
-  return PAFU_OK;
+  return check_step_alias(a, false);
 }
 
 }  // namespace
@@ -324,7 +421,8 @@ size_t pafu_sse_workspace_bytes(int L, int N) { return L > 0 && N > 0 ? sse_work
 
 int pafu_sse_score(void* stream, const void* Q, const void* K, int L, int N, int D, long long ld_q, long long ld_k,
                    int block_len, float softmax_scale, float* out, void* workspace, size_t workspace_bytes) {
-  if (L < 0 || N < 1 || N > 65535 || block_len < 1) return PAFU_ERR_SHAPE;
+  if (L < 0 || N < 1 || block_len < 1) return PAFU_ERR_SHAPE;
+  if (((long long)L / 32 + 1) * N > 0x7fffffffll) return PAFU_ERR_SHAPE;  // one-dimensional grid
   if (D != 64 && D != 128) return PAFU_ERR_SHAPE;
   if (L == 0) return PAFU_OK;
   if (!Q || !K || !out) return PAFU_ERR_NULL;
@@ -362,6 +460,10 @@ int pafu_step_layers(void* stream, const pafu_step_args* args, int n_layers) {
   if (n_layers > 0 && !args) return PAFU_ERR_NULL;
   for (int l = 0; l < n_layers; ++l) {  // validate every layer before enqueuing any
     int rc = check_step(&args[l]);
+    if (rc) return rc;
+  }
+  {
+    int rc = check_layers_alias(args, n_layers, -1);
     if (rc) return rc;
   }
   // The layers are independent, so the order of their stages is free: all scores first, then every layer's selection
@@ -404,6 +506,8 @@ int pafu_step_layers_shared(void* stream, const pafu_step_args* args, int n_laye
     rc = check_layer_kv(&args[l], idx);
     if (rc) return rc;
   }
+  rc = check_layers_alias(args, n_layers, index_layer);
+  if (rc) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   // ROLLOUT selects on the stored list, so the indices exist before any layer runs; the chunk's own scores are only
   // needed for the append.  SINGLE scores first.  Either way: scores, one selection, then every layer's cache.

@@ -438,6 +438,12 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnPara
       s_a[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], s_a[kb], 0, 0, 0);
     }
   }
+  // Step 0 refills ring slot 0 (K(kAtStages) replaces K(0)): every wave must have its K(0) fragments in registers
+  // before any wave issues that load.  The products above have consumed them, so one barrier here is enough; inside
+  // the loop the barrier that ends step t-1 plays this role for step t.
+  asm volatile("" : "+v"(s_a[0]), "+v"(s_a[1]));
+  __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
+  __builtin_amdgcn_s_barrier();
 
   // A wave whose 32 queries all lie past the end (the last query tile of a head is usually ragged) still loads its
   // share of every tile and joins every barrier, but does no arithmetic: on this chip energy is time.
@@ -515,13 +521,9 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnPara
 
 template <int D, bool OUT_F32, bool GATHER>
 int launch_variant(hipStream_t st, dim3 grid, const AttnParams& p) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(chunk_attention_kernel<D, OUT_F32, GATHER>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, attn_lds_bytes(D, GATHER));
-    if (e != hipSuccess) return record_hip_error(e);
-    attr_set = true;
-  }
+  static LdsLimit lds_limit;
+  const int rc = set_lds_limit(lds_limit, chunk_attention_kernel<D, OUT_F32, GATHER>, attn_lds_bytes(D, GATHER));
+  if (rc != PAFU_OK) return rc;
   hipLaunchKernelGGL((chunk_attention_kernel<D, OUT_F32, GATHER>), grid, dim3(kAtThreads),
                      attn_lds_bytes(D, GATHER), st, p);
   return check_launch();

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "pafu.h"
 
 namespace pafu {
@@ -15,6 +17,19 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 inline int check_launch() {
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? PAFU_OK : record_hip_error(e);
+}
+
+// Raises a kernel's dynamic LDS limit exactly once per process, whichever host thread launches it first.
+struct LdsLimit {
+  std::once_flag once;
+  hipError_t err = hipSuccess;
+};
+template <typename Kernel>
+inline int set_lds_limit(LdsLimit& state, Kernel kernel, int bytes) {
+  std::call_once(state.once, [&] {
+    state.err = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  });
+  return state.err == hipSuccess ? PAFU_OK : record_hip_error(state.err);
 }
 
 inline bool overlaps(const void* a, size_t a_bytes, const void* b, size_t b_bytes) {

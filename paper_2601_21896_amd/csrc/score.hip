@@ -5,12 +5,15 @@
 // tiny pre-kernel folds W2/b2 into one row w2bar[M] and a scalar (skipped when n_out == 1); the main
 // kernel then fuses layer 1, the activation, the dot with w2bar and the bias into one pass over X.
 //
-// bf16 path: layer 1 is a skinny dense contraction [M x F] . [F x T], so it runs on the matrix cores
-// (v_mfma_f32_32x32x16_bf16, fp32 accumulate).  Each wave owns 32 tokens and streams their feature
-// rows straight from HBM into MFMA B-operand registers (16 contiguous bytes per lane, read once);
-// W1 is staged through LDS in 64-feature slabs shared by the four waves of a workgroup.  H = W1.X is
-// produced as H^T tiles (rows = hidden units, columns = tokens), so one lane holds 16 hidden units of
-// ONE token per tile and the reduction over hidden units is almost entirely in-register.
+// bf16 paths: layer 1 is a skinny dense contraction [M x F] . [F x T], so it runs on the matrix cores
+// (v_mfma_f32_32x32x16_bf16, fp32 accumulate).  H = W1.X is produced as H^T tiles (rows = hidden units,
+// columns = tokens), so one lane holds 16 hidden units of ONE token per tile and the reduction over hidden
+// units is almost entirely in-register.
+//  - score_stream_kernel (M a multiple of 256): the measured path.  W1 and the features both stream
+//    global -> LDS through a ring of 64-feature slabs; a workgroup owns several 32-token tiles so that one W1
+//    fragment feeds several matrix instructions.  Described in detail above the kernel.
+//  - score_mfma_kernel (other M a multiple of 32): a wave owns 32 tokens and loads their feature rows straight
+//    into B-operand registers; W1 is staged through LDS in 64-feature slabs shared by the waves of a workgroup.
 //
 // generic path (fp32 inputs, or shapes the tiles do not divide): plain fp32 FMAs.
 #include "pafu_internal.h"
@@ -485,13 +488,9 @@ int launch_score(hipStream_t st, const void* x0, const void* x1, const void* x2,
     const int blocks = M / 32;
 #define PAFU_SCORE_CASE(MB)                                                                                          \
   do {                                                                                                               \
-    static bool attr_set = false;                                                                                    \
-    if (!attr_set) {                                                                                                 \
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(score_mfma_kernel<MB>),                       \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, sc_lds_bytes(MB));              \
-      if (e != hipSuccess) return record_hip_error(e);                                                               \
-      attr_set = true;                                                                                               \
-    }                                                                                                                \
+    static LdsLimit lds_limit;                                                                                       \
+    const int rc_ = set_lds_limit(lds_limit, score_mfma_kernel<MB>, sc_lds_bytes(MB));                               \
+    if (rc_ != PAFU_OK) return rc_;                                                                                  \
     hipLaunchKernelGGL(score_mfma_kernel<MB>, dim3(grid), dim3(kScThreads), sc_lds_bytes(MB), st,                    \
                        static_cast<const unsigned short*>(x0), static_cast<const unsigned short*>(x1),               \
                        static_cast<const unsigned short*>(x2), T, Fs, F, ld_x, static_cast<const unsigned short*>(W1), \
@@ -515,13 +514,9 @@ int launch_score(hipStream_t st, const void* x0, const void* x1, const void* x2,
       }
 #define PAFU_SCORE3_CASE(TT)                                                                                         \
   do {                                                                                                               \
-    static bool attr_set3 = false;                                                                                   \
-    if (!attr_set3) {                                                                                                \
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(score_stream_kernel<TT>),                     \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, s3_lds_bytes(TT));              \
-      if (e != hipSuccess) return record_hip_error(e);                                                               \
-      attr_set3 = true;                                                                                              \
-    }                                                                                                                \
+    static LdsLimit lds_limit3;                                                                                      \
+    const int rc_ = set_lds_limit(lds_limit3, score_stream_kernel<TT>, s3_lds_bytes(TT));                            \
+    if (rc_ != PAFU_OK) return rc_;                                                                                  \
     hipLaunchKernelGGL(score_stream_kernel<TT>, dim3((tiles + TT - 1) / TT), dim3(512), s3_lds_bytes(TT), st,        \
                        static_cast<const unsigned short*>(x0), static_cast<const unsigned short*>(x1),               \
                        static_cast<const unsigned short*>(x2), T, Fs, F, ld_x, static_cast<const unsigned short*>(W1), \

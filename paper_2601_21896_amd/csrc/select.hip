@@ -7,7 +7,7 @@
 // prefix scans provide, so the result depends only on the score bits, never on atomic arrival order.
 //
 // The whole score list is a few hundred KB at most (one fp32 per cached token), so the work is
-// latency-bound and one workgroup handles one list.  Lists of up to 81920 scores use the bit-sliced
+// latency-bound and one workgroup handles one list.  Lists of up to 98304 scores use the bit-sliced
 // kernel: each thread loads its 32 W consecutive keys ONCE and transposes them into 32 bit-planes of W
 // words; a radix-2 pass is then two instructions per word (and + popcount) plus one block-wide sum, and
 // the "greater" and "equal" masks the emit needs fall out of the 32 passes.  Longer lists fall back to
@@ -421,14 +421,9 @@ int launch_select_batch(hipStream_t st, const SelectJob* jobs, int count) {
     // the longest list picks the kernel (keys per thread x threads must cover it)
 #define PAFU_SELECT_CASE(W, NT)                                                                                   \
   do {                                                                                                            \
-    static bool attr_set = false;                                                                                 \
-    if (!attr_set) {                                                                                              \
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(select_bitslice_kernel<W, NT>),            \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize,                              \
-                                         select_bitslice_lds_bytes(NT));                                          \
-      if (e != hipSuccess) return record_hip_error(e);                                                            \
-      attr_set = true;                                                                                            \
-    }                                                                                                             \
+    static LdsLimit lds_limit;                                                                                    \
+    const int rc_ = set_lds_limit(lds_limit, select_bitslice_kernel<W, NT>, select_bitslice_lds_bytes(NT));       \
+    if (rc_ != PAFU_OK) return rc_;                                                                               \
     hipLaunchKernelGGL((select_bitslice_kernel<W, NT>), dim3(m), dim3(NT), select_bitslice_lds_bytes(NT), st, B); \
   } while (0)
     if (n_max <= 256 * 32) PAFU_SELECT_CASE(1, 256);

@@ -318,13 +318,9 @@ int launch_pass(hipStream_t st, const SseParams& p) {
   // One 32-row group per wave and two workgroups per CU.  Two groups per wave (half the LDS reads per matrix
   // instruction, one workgroup per CU) measured the same: LDS read bandwidth is not what bounds the passes.
   constexpr int HT = 1;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(sse_pass_kernel<D, COLMAX, HT>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, sse_lds_bytes(D));
-    if (e != hipSuccess) return record_hip_error(e);
-    attr_set = true;
-  }
+  static LdsLimit lds_limit;
+  const int rc = set_lds_limit(lds_limit, sse_pass_kernel<D, COLMAX, HT>, sse_lds_bytes(D));
+  if (rc != PAFU_OK) return rc;
   constexpr int HELD = kSseWaves * 32 * HT;
   const int grid = ((p.L + HELD - 1) / HELD) * p.N;
   hipLaunchKernelGGL((sse_pass_kernel<D, COLMAX, HT>), dim3(grid), dim3(kSseThreads), sse_lds_bytes(D), st, p);

@@ -143,6 +143,52 @@ def test_step_rejects_bad_arguments():
     assert lib.pafu_step(None, ctypes.byref(a)) == -2                             # negative frame sink
 
 
+def _fake_step(base, mode=0, n=100, Lc=20, k=50, N=2, D=64):
+    """A pafu_step_args that passes every check, over fake device addresses 1 MiB apart from `base`."""
+    a = binding.pafu_step_args()
+    a.mode, a.N, a.D, a.n, a.Lc, a.k, a.block_len = mode, N, D, n, Lc, k, Lc
+    a.M, a.n_out, a.act, a.n_seg, a.Fs, a.x_dtype, a.out_dtype = 32, 1, 0, 1, N * D, 0, 0
+    a.ld_x = a.ld_cache = a.ld_out = a.ld_chunk = a.ld_o = N * D
+    slot = iter(range(base, base + 64 * 0x100000, 0x100000))
+    a.x_cache[0], a.x_chunk[0] = next(slot), next(slot)
+    a.W1, a.W2 = next(slot), next(slot)
+    a.K_cache, a.V_cache, a.SL_in = next(slot), next(slot), next(slot)
+    a.Q, a.K_chunk, a.V_chunk = next(slot), next(slot), next(slot)
+    a.scores, a.ids = next(slot), next(slot)
+    a.K_out, a.V_out, a.SL_out, a.O = next(slot), next(slot), next(slot), next(slot)
+    return a
+
+
+def test_step_rejects_aliased_buffers():
+    lib = binding.library()
+    row = 2 * 64 * 2                                    # bytes per token of K / V
+    # ROLLOUT appends the chunk behind the k retained rows: an input inside that region is an alias too
+    a = _fake_step(A, mode=1)
+    a.K_chunk = a.K_out + 50 * row
+    assert lib.pafu_step(None, ctypes.byref(a)) == -6
+    a = _fake_step(A, mode=1)
+    a.SL_in = a.SL_out + 52 * 4                          # the appended scores would overwrite the stored list
+    assert lib.pafu_step(None, ctypes.byref(a)) == -6
+    a = _fake_step(A)
+    a.O = a.V_chunk
+    assert lib.pafu_step(None, ctypes.byref(a)) == -6
+    a = _fake_step(A)
+    a.V_out = a.K_out + 16                               # overlapping rows of the two output slabs
+    assert lib.pafu_step(None, ctypes.byref(a)) == -6
+    # multi-layer steps reorder the stages across layers: a buffer shared between layers is an error
+    for field in ("scores", "ids", "SL_out", "K_out", "O"):
+        pair = (binding.pafu_step_args * 2)(_fake_step(A), _fake_step(A + 0x8000000))
+        setattr(pair[1], field, getattr(pair[0], field))
+        assert lib.pafu_step_layers(None, pair, 2) == -6, field
+    pair = (binding.pafu_step_args * 2)(_fake_step(A), _fake_step(A + 0x8000000))
+    pair[1].K_cache = pair[0].K_out                      # one layer's output is another layer's input
+    assert lib.pafu_step_layers(None, pair, 2) == -6
+    assert lib.pafu_step_layers_shared(None, pair, 2, 1) == -6
+    pair = (binding.pafu_step_args * 2)(_fake_step(A), _fake_step(A + 0x8000000))
+    pair[0].O = pair[1].O
+    assert lib.pafu_step_layers_shared(None, pair, 2, 1) == -6
+
+
 def test_sse_rejects_bad_arguments_and_reports_its_workspace():
     lib = binding.library()
     assert binding.pafu_sse_workspace_bytes(1000, 3) == 16 * 3 * 1000
