@@ -75,6 +75,20 @@ int pafu_score(void* stream, const void* x0, const void* x1, const void* x2, int
                const float* b2, int M, int n_out, int act, float* out, void* workspace,
                size_t workspace_bytes);
 
+/* pafu_score_static - pafu_score for callers that cannot allocate or carry a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments without the workspace pair, same kernels,
+ * same results; the output-averaged second layer lives in a static device array inside the library
+ * (PAFU_SCORE_STATIC_MAX_M + 1 floats, 256-byte aligned, one copy per GPU, held until the process ends).  The call
+ * allocates nothing and synchronises nothing.  M > PAFU_SCORE_STATIC_MAX_M returns PAFU_ERR_WORKSPACE with nothing
+ * enqueued.  Every call on a GPU shares that GPU's array: calls that overlap in time on one GPU (different streams
+ * or host threads) race on it unless n_out == 1, where the array is not used; each call rewrites all M + 1 entries it
+ * reads, so nothing needs clearing between calls.
+ */
+#define PAFU_SCORE_STATIC_MAX_M 8192
+int pafu_score_static(void* stream, const void* x0, const void* x1, const void* x2, int n_seg, int T, int Fs,
+                      long long ld_x, int x_dtype, const void* W1, const float* b1, const float* W2,
+                      const float* b2, int M, int n_out, int act, float* out);
+
 /* ------------------------------------------------------------------------------------------
  * pafu_select_topk - top-k retention, Sec. 3.4 inference paragraph; Alg. 2 (Top-k of the score list).
  *

@@ -21,7 +21,7 @@ PAFU_MODE_SINGLE, PAFU_MODE_ROLLOUT = 0, 1
 
 SYMBOLS = (
     "pafu_strerror", "pafu_last_hip_error", "pafu_version",
-    "pafu_score_workspace_bytes", "pafu_score",
+    "pafu_score_workspace_bytes", "pafu_score", "pafu_score_static",
     "pafu_select_workspace_bytes", "pafu_select_topk", "pafu_select_topk_pinned",
     "pafu_compact_kv",
     "pafu_attention_workspace_bytes", "pafu_chunk_attention", "pafu_chunk_attention_gather",
@@ -77,6 +77,9 @@ def _lib():
         lib.pafu_score.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_longlong, c_int,
                                    c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_void_p, c_void_p,
                                    c_size_t]
+        lib.pafu_score_static.restype = c_int
+        lib.pafu_score_static.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_longlong, c_int,
+                                          c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_void_p]
         lib.pafu_select_workspace_bytes.restype = c_size_t
         lib.pafu_select_workspace_bytes.argtypes = [c_int]
         lib.pafu_select_topk.restype = c_int
@@ -178,6 +181,20 @@ def pafu_score(x_segs, W1, b1, W2, b2, out, act=PAFU_ACT_SILU, workspace=None, s
                            _dtype_code(x0), _ptr(W1), _ptr(b1), _ptr(W2), _ptr(b2), M, n_out, act, _ptr(out),
                            _ptr(workspace), ws_bytes)
     _check(rc, "pafu_score")
+    return out
+
+
+def pafu_score_static(x_segs, W1, b1, W2, b2, out, act=PAFU_ACT_SILU, stream=None, T=None):
+    """pafu_score without a workspace: the library's static device scratch holds the folded second layer."""
+    if not isinstance(x_segs, (tuple, list)):
+        x_segs = (x_segs,)
+    x0 = x_segs[0]
+    T = x0.shape[0] if T is None else T
+    ptrs = [_ptr(x) for x in x_segs] + [None] * (3 - len(x_segs))
+    rc = _lib().pafu_score_static(_stream(stream), ptrs[0], ptrs[1], ptrs[2], len(x_segs), T, x0.shape[1],
+                                  x0.stride(0), _dtype_code(x0), _ptr(W1), _ptr(b1), _ptr(W2), _ptr(b2), W1.shape[0],
+                                  W2.shape[0], act, _ptr(out))
+    _check(rc, "pafu_score_static")
     return out
 
 

@@ -28,7 +28,9 @@ int check_score(const void* x0, const void* x1, const void* x2, int n_seg, int T
   if (!aligned16(x0) || (n_seg > 1 && !aligned16(x1)) || (n_seg > 2 && !aligned16(x2)) || !aligned16(W1) ||
       !aligned16(W2) || (ld_x * eb) % 16 != 0)
     return PAFU_ERR_ALIGN;
-  if (n_out > 1 && (ws == nullptr || ws_bytes < pafu_score_workspace_bytes(M))) return PAFU_ERR_WORKSPACE;
+  // ws_bytes == SIZE_MAX: the caller brings its own scratch (pafu_score_static)
+  if (n_out > 1 && ws_bytes != SIZE_MAX && (ws == nullptr || ws_bytes < pafu_score_workspace_bytes(M)))
+    return PAFU_ERR_WORKSPACE;
   return PAFU_OK;
 }
 
@@ -346,6 +348,17 @@ int pafu_score(void* stream, const void* x0, const void* x1, const void* x2, int
   if (rc) return rc;
   return launch_score(static_cast<hipStream_t>(stream), x0, x1, x2, n_seg, T, Fs, ld_x, x_dtype, W1, b1, W2, b2, M,
                       n_out, act, out, workspace);
+}
+
+int pafu_score_static(void* stream, const void* x0, const void* x1, const void* x2, int n_seg, int T, int Fs,
+                      long long ld_x, int x_dtype, const void* W1, const float* b1, const float* W2, const float* b2,
+                      int M, int n_out, int act, float* out) {
+  // same validation as pafu_score, with the library's own scratch standing in for the workspace
+  int rc = check_score(x0, x1, x2, n_seg, T, Fs, ld_x, x_dtype, W1, W2, M, n_out, act, out, nullptr, SIZE_MAX);
+  if (rc) return rc;
+  if (M > PAFU_SCORE_STATIC_MAX_M) return PAFU_ERR_WORKSPACE;
+  return launch_score_static(static_cast<hipStream_t>(stream), x0, x1, x2, n_seg, T, Fs, ld_x, x_dtype, W1, b1, W2, b2,
+                             M, n_out, act, out);
 }
 
 size_t pafu_select_workspace_bytes(int n) {

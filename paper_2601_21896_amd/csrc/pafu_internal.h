@@ -60,6 +60,10 @@ int launch_select(hipStream_t st, const float* scores, int n, int k, int n_pinne
 int launch_score(hipStream_t st, const void* x0, const void* x1, const void* x2, int n_seg, int T, int Fs,
                  long long ld_x, int x_dtype, const void* W1, const float* b1, const float* W2, const float* b2,
                  int M, int n_out, int act, float* out, void* ws);
+// The same with the folded second layer in the library's own static device array (no workspace, no allocation).
+int launch_score_static(hipStream_t st, const void* x0, const void* x1, const void* x2, int n_seg, int T, int Fs,
+                        long long ld_x, int x_dtype, const void* W1, const float* b1, const float* W2,
+                        const float* b2, int M, int n_out, int act, float* out);
 size_t sse_workspace_bytes(int L, int N);
 int launch_sse(hipStream_t st, const void* Q, const void* K, int L, int N, int D, long long ld_q, long long ld_k,
                int block_len, float scale, float* out, void* workspace);

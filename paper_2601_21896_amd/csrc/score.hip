@@ -465,7 +465,44 @@ __global__ __launch_bounds__(512, 1) void score_stream_kernel(
   }
 }
 
+// Scratch of pafu_score_static: the output-averaged second layer (M weights + 1 bias) that pafu_score keeps in its
+// caller-provided workspace.  One copy per GPU, held until the process ends; every call on a GPU shares it.
+static __device__ __align__(256) float scratch[PAFU_SCORE_STATIC_MAX_M + 1];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+float* g_scratch_ptr[kMaxDevices] = {};  // device address of `scratch` on each GPU (the array's name is only a
+                                         // host-side handle: kernels are given these addresses)
+
+// Device address of `scratch` on the current GPU, looked up once per device.
+int score_scratch(float** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return record_hip_error(e);
+  if (dev < 0 || dev >= kMaxDevices) return PAFU_ERR_SHAPE;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return record_hip_error(e);
+    if (ptr == nullptr) return record_hip_error(hipErrorInvalidSymbol);
+    g_scratch_ptr[dev] = static_cast<float*>(ptr);
+  }
+  *out = g_scratch_ptr[dev];
+  return PAFU_OK;
+}
+
 }  // namespace
+
+int launch_score_static(hipStream_t st, const void* x0, const void* x1, const void* x2, int n_seg, int T, int Fs,
+                        long long ld_x, int x_dtype, const void* W1, const float* b1, const float* W2,
+                        const float* b2, int M, int n_out, int act, float* out) {
+  if (M > PAFU_SCORE_STATIC_MAX_M) return PAFU_ERR_WORKSPACE;
+  float* ws = nullptr;
+  const int rc = score_scratch(&ws);
+  if (rc != PAFU_OK) return rc;
+  return launch_score(st, x0, x1, x2, n_seg, T, Fs, ld_x, x_dtype, W1, b1, W2, b2, M, n_out, act, out, ws);
+}
 
 int launch_score(hipStream_t st, const void* x0, const void* x1, const void* x2, int n_seg, int T, int Fs,
                  long long ld_x, int x_dtype, const void* W1, const float* b1, const float* W2, const float* b2, int M,
