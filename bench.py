@@ -6,9 +6,11 @@ chunk tokens with the S-MLP, select the top-k cached tokens, compact K/V/SL, and
 queries over the retained cache plus the chunk (pafu_step, SINGLE mode).  The default workload is the
 Wan-1.3B-shaped single layer in bf16 (12 heads x 128, 32760 cached + 4680 chunk tokens, budget 16380).
 
-Prints ONE JSON line: ms per step (inputs resident in HBM), a per-stage breakdown measured with events
-on the launch stream, the roofline of the dominant kernel (attention, dense bf16 MFMA), and the fp64
-oracle timed on this machine's host cores on a bounded sample of the same workload.
+Prints ONE JSON line: ms per step (inputs resident in HBM), a per-stage breakdown and the duration of the
+dominant kernel (attention, dense bf16 MFMA) measured with events that the library records on the launch
+stream inside whole steps, the parity of the last step's buffers against the fp64 oracle, a sustained
+figure from a run of at least a second, and the oracle timed on this machine's host cores.  The process exits
+with status 1 when a parity figure is out of tolerance.
 """
 
 from __future__ import annotations
@@ -25,13 +27,53 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+METRIC = "ms per AR chunk step (score+select+compact+attn), MFMA util and HBM GB/s"
+TOL = {"score_max_abs": 1e-3, "attn_max_abs": 2e-2, "attn_rel_fro": 5e-3}   # the benchmark spec's tolerances
 
-# HBM bytes per attention launch from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE, scaled by a copy kernel);
-# filled from the summaries under profiles/ (None = not measured for that workload).
-MEASURED_ATTENTION_TRAFFIC_BYTES = {
+# HBM bytes per attention launch from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE, scaled by a copy kernel): a figure
+# from a separate counter run whose summary is tracked under profiles/, NOT re-measured by this run.
+ATTENTION_TRAFFIC = {
     # profiles/step_C1_hbm_traffic_pmc.md: 107168.7 KiB x 1.98 fetched + 14042.1 KiB written
-    ("C1", True): int((107168.7 * 1.98 + 14042.1) * 1024),
+    ("C1", True): (int((107168.7 * 1.98 + 14042.1) * 1024), "profiles/step_C1_hbm_traffic_pmc.md"),
 }
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="C1", choices=["C1", "C4", "C2", "C0", "C3", "SSE", "ATTN"])
+    ap.add_argument("--budget", type=int, default=0, help="C3 only: cache budget k in tokens (default 8 frames = 12480)")
+    ap.add_argument("--block-len", type=int, default=0, help="L_B (0 = chunk length, the paper's setting)")
+    ap.add_argument("--structure", default="uniform", choices=["uniform", "coherent"])
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle leg (then no parity figures either)")
+    ap.add_argument("--sets", type=int, default=3, help="input buffer sets rotated between steps")
+    ap.add_argument("--shared-index", action="store_true",
+                    help="C2 only: score + select once on the last layer, every layer reuses its indices (Sec. 3.3)")
+    ap.add_argument("--head", default="benchmark", choices=["benchmark", "paper"],
+                    help="S-MLP widths: the benchmark's (F = H, M from the config, 1 output) or App. A's "
+                         "([Q|K|V] = 3H inputs, 1024 hidden, 12 outputs averaged)")
+    ap.add_argument("--pinned", type=int, default=0, help="frame sink: cached tokens [0, pinned) are never evicted")
+    ap.add_argument("--sustained-s", type=float, default=1.0,
+                    help="length of the extra back-to-back run behind sustained_ms_per_step (0 = skip)")
+    ap.add_argument("--chunk-frames", type=int, default=0, help="ATTN only: frames per chunk (default 3)")
+    ap.add_argument("--data", default="normal", choices=["normal", "zeros"],
+                    help="ATTN only: N(0,1) tensors (default) or all-zero tensors (same instructions, no operand toggling)")
+    ap.add_argument("--library", default="", help="load this build of libpafu.so instead of the in-tree default")
+    return ap.parse_args()
+
+
+def event_pair_ms(evs):
+    return [evs[i].elapsed_time(evs[i + 1]) for i in range(len(evs) - 1)]
+
+
+def new_events(torch, count):
+    """Timing events whose handles exist (torch creates them lazily at the first record)."""
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(count)]
+    for e in evs:
+        e.record()
+    return evs
 
 
 def sse(a, torch, np, B, wl):
@@ -71,28 +113,57 @@ def sse(a, torch, np, B, wl):
         "cpu_baseline": None}))
 
 
-def parse():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="C1", choices=["C1", "C4", "C2", "C0", "C3", "SSE"])
-    ap.add_argument("--budget", type=int, default=0, help="C3 only: cache budget k in tokens (default 8 frames = 12480)")
-    ap.add_argument("--block-len", type=int, default=0, help="L_B (0 = chunk length, the paper's setting)")
-    ap.add_argument("--structure", default="uniform", choices=["uniform", "coherent"])
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--sets", type=int, default=3, help="input buffer sets rotated between steps")
-    ap.add_argument("--shared-index", action="store_true",
-                    help="C2 only: score + select once on the last layer, every layer reuses its indices (Sec. 3.3)")
-    ap.add_argument("--head", default="benchmark", choices=["benchmark", "paper"],
-                    help="S-MLP widths: the benchmark's (F = H, M from the config, 1 output) or App. A's "
-                         "([Q|K|V] = 3H inputs, 1024 hidden, 12 outputs averaged)")
-    ap.add_argument("--pinned", type=int, default=0, help="frame sink: cached tokens [0, pinned) are never evicted")
-    return ap.parse_args()
+def attention_only(a, torch, np, B, wl):
+    """The attention stage alone at the Wan-1.3B layer shape (retained cache 16380 + chunk), launched back to back:
+    the workload of the kernel studies under profiles/ (N(0,1) or all-zero tensors, any build of the library)."""
+    cfg = wl.C1
+    dev = "cuda:0"
+    N, D, k = cfg.N, cfg.D, cfg.k
+    Lc = (a.chunk_frames or cfg.chunk_frames) * cfg.frame_tokens
+    L_B = a.block_len or Lc
+    g = torch.Generator(device=dev)
+    g.manual_seed(wl.BASE_SEED)
+
+    def tensor(rows):
+        if a.data == "zeros":
+            return torch.zeros(rows, N, D, device=dev, dtype=torch.bfloat16)
+        return torch.randn(rows, N, D, device=dev, generator=g).to(torch.bfloat16)
+    sets = [(tensor(Lc), tensor(k), tensor(k), tensor(Lc), tensor(Lc)) for _ in range(max(1, a.sets))]
+    O = torch.empty(Lc, N, D, device=dev, dtype=torch.bfloat16)
+    ws = torch.empty(B.pafu_attention_workspace_bytes(Lc, N, D), dtype=torch.uint8, device=dev)
+
+    def run(i):
+        Q, Kc, Vc, Kn, Vn = sets[i % len(sets)]
+        B.pafu_chunk_attention(Q, Kc, Vc, k, Kn, Vn, L_B, O, workspace=ws)
+    for i in range(a.warmup):
+        run(i)
+    torch.cuda.synchronize()
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(a.steps + 1)]
+    evs[0].record()
+    for i in range(a.steps):
+        run(i)
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    t = np.array(event_pair_ms(evs))
+    ms = float(evs[0].elapsed_time(evs[-1]) / a.steps)
+    pairs = Lc * k + sum(min(Lc, (i // L_B + 1) * L_B) for i in range(Lc))
+    flops = 4.0 * pairs * D * N
+    print(json.dumps({
+        "metric": "ms per chunk-attention launch", "value": ms, "unit": "ms", "n_gpus": 1, "steps": a.steps,
+        "warmup": a.warmup, "ms_per_step": ms, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic (%s)" % ("N(0,1)" if a.data == "normal" else "all zeros"),
+        "config": {"workload": "ATTN: %d queries x (%d retained + %d chunk keys), %d heads x %d, L_B=%d" %
+                               (Lc, k, Lc, N, D, L_B), "library": a.library or "in-tree libpafu.so"},
+        "median_ms": float(np.median(t)), "min_ms": float(t.min()),
+        "roofline": {"kernel": "chunk_attention_kernel", "bound": "mfma", "achieved": flops / ms / 1e9,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": flops / ms / 1e9 / PEAK_BF16_TFLOPS,
+                     "traffic": None, "flops_per_launch": flops, "avg_launch_ms": ms},
+        "cpu_baseline": None}))
 
 
 def rollout(a, torch, np, B, wl):
-    """C3: 60 sequential chunks at the Wan-1.3B layer shapes, fixed budget; steady-state ms per step."""
+    """C3: 60 sequential chunks at the Wan-1.3B layer shapes, fixed budget; steady-state ms per step, per-stage
+    durations from the library's stage events, peak cache bytes."""
     dev = "cuda:0"
     bf = torch.bfloat16
     cfg = wl.C1
@@ -112,41 +183,53 @@ def rollout(a, torch, np, B, wl):
                   SL=torch.zeros(cap, device=dev)) for _ in range(2)]
     ids = torch.empty(max(k, 1), dtype=torch.int32, device=dev)
     O = torch.empty(Lc, N, D, device=dev, dtype=bf)
-    times, sizes = [], []
+    ws = torch.empty(B.pafu_attention_workspace_bytes(Lc, N, D), dtype=torch.uint8, device=dev)
+    stage_names = ("score", "select", "compact", "attention")
+    times, sizes, stage_t = [], [], []
     for rep in range(2):    # first pass warms up, second is timed
         n, cur = 0, 0
-        times, sizes = [], []
+        times, sizes, stage_t = [], [], []
         for step in range(n_chunks):
             c = pool[step % len(pool)]
             src, dst = slabs[cur], slabs[1 - cur]
             args = B.make_step_args(B.PAFU_MODE_ROLLOUT, N, D, n, Lc, k, Lc, None, c["X"], W1, None, W2, None, src["K"],
                                     src["V"], src["SL"], c["Q"], c["K"], c["V"], None, ids, dst["K"], dst["V"],
-                                    dst["SL"], O, n_pinned=a.pinned)
+                                    dst["SL"], O, n_pinned=a.pinned, workspace=ws)
+            sev = new_events(torch, 5)
+            B.set_stage_events(args, sev)
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
             B.pafu_step(args)
             e1.record()
             torch.cuda.synchronize()
             times.append(e0.elapsed_time(e1))
+            stage_t.append(event_pair_ms(sev))
             n = min(k, n) + Lc
             sizes.append(n)
             cur = 1 - cur
     steady = times[5:]
+    st = np.array(stage_t[5:])
     n_steady = sizes[-1]
-    n_kept = min(k, n_steady)
+    n_kept = min(k, n_steady - Lc)
     flops = 4.0 * Lc * (n_kept + Lc) * D * N
+    attn_ms = float(np.mean(st[:, 3]))
     peak_cache = 2 * (cap * N * D * 2 * 2 + cap * 4)
+    bytes_compact = 2 * (2 * n_kept * N * D * 2) + 3 * n_kept * 4
     out = {
-        "metric": "ms per AR chunk step (score+select+compact+attn), MFMA util and HBM GB/s", "value": float(np.median(steady)), "unit": "ms",
+        "metric": METRIC, "value": float(np.median(steady)), "unit": "ms",
         "n_gpus": 1, "steps": len(steady), "warmup": n_chunks + 5, "ms_per_step": float(np.median(steady)),
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "C3: %d-chunk rollout, 12 heads x 128, chunk %d queries, budget %d tokens, steady cache "
                                "%d tokens, S-MLP %d->%d->1" % (n_chunks, Lc, k, n_steady, H, M)},
         "min_ms": float(np.min(steady)), "first_steps_ms": [float(x) for x in times[:5]], "cache_sizes_first_steps": sizes[:6],
         "peak_cache_bytes": peak_cache,
-        "roofline": {"kernel": "chunk_attention_kernel", "bound": "mfma", "achieved": None, "peak": PEAK_BF16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": None, "traffic": None, "flops_per_launch": flops,
-                     "note": "whole-step time only; per-kernel times come from the rocprofv3 summary"},
+        "stages": {s: {"ms": float(np.mean(st[:, j])), "min_ms": float(np.min(st[:, j]))} for j, s in enumerate(stage_names)},
+        "compact_GB/s": bytes_compact / float(np.mean(st[:, 2])) / 1e6 if n_kept else None,
+        "roofline": {"kernel": "chunk_attention_kernel", "bound": "mfma", "achieved": flops / attn_ms / 1e9,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": flops / attn_ms / 1e9 / PEAK_BF16_TFLOPS,
+                     "traffic": None, "flops_per_launch": flops, "avg_launch_ms": attn_ms,
+                     "note": "steady-state launches (cache %d + chunk %d keys), events recorded by the library "
+                             "around the attention launch inside each step" % (n_kept, Lc)},
         "cpu_baseline": None,
     }
     print(json.dumps(out))
@@ -167,6 +250,8 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
+    if a.library:
+        B.LIB_PATH = os.path.abspath(a.library)
     B.library()
     dev = "cuda:0"
     torch.cuda.set_device(0)
@@ -177,14 +262,16 @@ def main():
     if a.workload == "SSE":
         sse(a, torch, np, B, wl)
         return
+    if a.workload == "ATTN":
+        attention_only(a, torch, np, B, wl)
+        return
     n_layers = wl.C2_LAYERS if a.workload == "C2" else 1
     cfg = wl.C1 if a.workload == "C2" else wl.CONFIGS[a.workload]
     N, D, n, Lc, k, H, M = cfg.N, cfg.D, cfg.n, cfg.Lc, cfg.k, cfg.H, cfg.M
     L_B = a.block_len or Lc
     n_kept = min(k, n)
     bf = torch.bfloat16
-    x_dt = bf if cfg.dtype == "bf16" else torch.float32
-    q = "bf16" if cfg.dtype == "bf16" else None
+    is_bf16 = cfg.dtype == "bf16"
 
     def to_dev(arr, bf16=False):
         t = torch.from_numpy(np.ascontiguousarray(arr)).to(dev)
@@ -194,12 +281,14 @@ def main():
     # distribution, different addresses) so that no step re-reads what the previous one left in cache
     t0 = time.time()
     d = wl.make_layer_inputs(cfg, structure=a.structure)
+    # the tiny config is generated in fp32: Q/K/V are rounded to bf16 once at the boundary, features stay fp32
+    kvq = {x: (d[x] if is_bf16 else wl.round_to_bf16(d[x])) for x in ("K_cache", "V_cache", "Q", "K_chunk", "V_chunk")}
     base = dict(
-        X=to_dev(np.concatenate([d["X_cache"], d["X_chunk"]]), cfg.dtype == "bf16"),
-        K=to_dev(d["K_cache"], True), V=to_dev(d["V_cache"], True),
-        Q=to_dev(d["Q"], True), Kn=to_dev(d["K_chunk"], True), Vn=to_dev(d["V_chunk"], True),
+        X=to_dev(np.concatenate([d["X_cache"], d["X_chunk"]]), is_bf16),
+        K=to_dev(kvq["K_cache"], True), V=to_dev(kvq["V_cache"], True),
+        Q=to_dev(kvq["Q"], True), Kn=to_dev(kvq["K_chunk"], True), Vn=to_dev(kvq["V_chunk"], True),
     )
-    W1 = to_dev(d["W1"], cfg.dtype == "bf16")
+    W1 = to_dev(d["W1"], is_bf16)
     W2, b1, b2 = to_dev(d["W2"]), None, None
     paper_head = a.head == "paper"
     n_seg = 3 if paper_head else 1
@@ -235,7 +324,10 @@ def main():
         cur["x_cache"], cur["x_chunk"] = feature_segments(cur["X"])
         cur["x_all"] = tuple(torch.cat([c_, n_]) for c_, n_ in zip(cur["x_cache"], cur["x_chunk"])) if paper_head \
             else (cur["X"],)
-        cur["ws"] = torch.empty(M + 64, device=dev)
+        # scoring part (the output-averaged second layer) + the attention launch's partial-result slots; the layers
+        # of a multi-layer step share one
+        cur["ws"] = torch.empty((M + 64) * 4 + B.pafu_attention_workspace_bytes(Lc, N, D) + 512, dtype=torch.uint8,
+                                device=dev) if (s == 0 or n_layers == 1) else sets[0]["ws"]
         cur["args"] = B.make_step_args(B.PAFU_MODE_SINGLE, N, D, n, Lc, k, L_B, cur["x_cache"], cur["x_chunk"], W1, b1,
                                        W2, b2, cur["K"], cur["V"], None, cur["Q"], cur["Kn"], cur["Vn"], cur["scores"],
                                        cur["ids"], cur["K_out"], cur["V_out"], cur["SL_out"], cur["O"],
@@ -243,16 +335,18 @@ def main():
         sets.append(cur)
     torch.cuda.synchronize()
     gen_s = time.time() - t0
+    shared = a.shared_index and n_layers > 1
+    idx_layer = n_layers - 1
 
     def run_step(i):
         if n_layers == 1:
             B.pafu_step(sets[i % n_sets]["args"])
-        elif a.shared_index:
-            B.pafu_step_layers_shared([s["args"] for s in sets], n_layers - 1)
+        elif shared:
+            B.pafu_step_layers_shared([s["args"] for s in sets], idx_layer)
         else:
             B.pafu_step_layers([s["args"] for s in sets])
 
-    # ---- whole-step timing
+    # ---- whole-step timing: the headline.  K steps between two events, nothing else on the stream.
     for i in range(a.warmup):
         run_step(i)
     torch.cuda.synchronize()
@@ -266,44 +360,70 @@ def main():
     wall_ms = (time.perf_counter() - t_start) * 1e3 / a.steps
     ms_per_step = ev0.elapsed_time(ev1) / a.steps
 
-    # ---- per-stage timing (same buffers, stage entry points, events on the launch stream)
-    stage_names = ("score", "select", "compact", "attention")
-    stage_ms = {s: [] for s in stage_names}
-    reps = max(a.steps, 10) if n_layers == 1 else 2
-
-    def stage_calls(cur):
-        return (
-            lambda: B.pafu_score(cur["x_all"], W1, b1, W2, b2, cur["scores"], workspace=cur["ws"]),
-            lambda: B.pafu_select_topk(cur["scores"], k, cur["ids"], n=n),
-            lambda: B.pafu_compact_kv(cur["K"], cur["V"], cur["scores"], cur["ids"], n_kept, cur["K_out"], cur["V_out"],
-                                      cur["SL_out"]),
-            lambda: B.pafu_chunk_attention(cur["Q"], cur["K_out"], cur["V_out"], n_kept, cur["Kn"], cur["Vn"], L_B,
-                                           cur["O"]),
-        )
-
-    # The repetitions are enqueued back to back, like the timed steps above, and read after one synchronisation at
-    # the end, so that the stage durations are taken at the same sustained clocks as the whole-step figure.
+    # ---- the same steps again with the library's stage events attached: every kernel of every step is bracketed by
+    # HIP events that pafu_step itself records on the launch stream (no host round trip between the stages).
     recorded = []
-    for i in range(reps + 2):
-        for cur in (sets if n_layers > 1 else [sets[i % n_sets]]):
-            evs = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
-            calls = stage_calls(cur)
-            evs[0].record()
-            for j, c in enumerate(calls):
-                c()
-                evs[j + 1].record()
-            if i >= 2:
-                recorded.append(evs)
+    for i in range(a.steps):
+        layers = sets if n_layers > 1 else [sets[i % n_sets]]
+        step_evs = []
+        for s_ in layers:
+            sev = new_events(torch, 5)
+            B.set_stage_events(s_["args"], sev)
+            step_evs.append(sev)
+        eva, evb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        eva.record()
+        run_step(i)
+        evb.record()
+        recorded.append((eva, evb, step_evs))
     torch.cuda.synchronize()
-    for evs in recorded:
-        for j, s in enumerate(stage_names):
-            stage_ms[s].append(evs[j].elapsed_time(evs[j + 1]))
-    avg = {s: float(np.mean(v)) for s, v in stage_ms.items()}
-    mn = {s: float(np.min(v)) for s, v in stage_ms.items()}
+    for s_ in sets:
+        B.set_stage_events(s_["args"], [None] * 5)
+    ms_with_events = float(np.mean([x.elapsed_time(y) for x, y, _ in recorded]))
+    attn_ms = [sev[3].elapsed_time(sev[4]) for _, _, se in recorded for sev in se]
+    if n_layers == 1:
+        score_ms = [se[0][0].elapsed_time(se[0][1]) for _, _, se in recorded]
+        select_ms = [se[0][1].elapsed_time(se[0][2]) for _, _, se in recorded]
+        compact_ms = [se[0][2].elapsed_time(se[0][3]) for _, _, se in recorded]
+        select_note = None
+    else:
+        # Multi-layer steps: all scoring first, then ONE selection launch for up to 32 layers, then compaction and
+        # attention layer by layer.  A layer's compaction = end of the previous layer's attention to the start of its
+        # own; the selection launch = end of the last scoring to the start of layer 0's attention, less one compaction.
+        scoring = [idx_layer] if shared else list(range(n_layers))
+        score_ms = [se[l][0].elapsed_time(se[l][1]) for _, _, se in recorded for l in scoring]
+        compact_ms = [se[l][4].elapsed_time(se[l + 1][3]) for _, _, se in recorded for l in range(n_layers - 1)]
+        select_ms = [max(0.0, se[scoring[-1]][1].elapsed_time(se[0][3]) - float(np.mean(compact_ms))) for _, _, se in recorded]
+        select_note = "one launch per step for %s" % ("the index layer" if shared else "all %d layers" % n_layers)
+    avg = {"score": float(np.mean(score_ms)), "select": float(np.mean(select_ms)), "compact": float(np.mean(compact_ms)),
+           "attention": float(np.mean(attn_ms))}
+    mn = {"score": float(np.min(score_ms)), "select": float(np.min(select_ms)), "compact": float(np.min(compact_ms)),
+          "attention": float(np.min(attn_ms))}
+
+    # ---- the floor of a stage between two events on this stream: an empty kernel
+    probe = [torch.cuda.Event(enable_timing=True) for _ in range(41)]
+    probe[0].record()
+    for i in range(40):
+        B.pafu_launch_probe()
+        probe[i + 1].record()
+    torch.cuda.synchronize()
+    empty_ms = float(np.median(event_pair_ms(probe)))
+
+    # ---- sustained: at least --sustained-s seconds of steps launched back to back (the chip's power management
+    # averages over a longer window than the headline's K steps)
+    sustained = None
+    if a.sustained_s > 0:
+        n_sus = max(a.steps, int(a.sustained_s * 1e3 / ms_per_step) + 1)
+        s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s0.record()
+        for i in range(n_sus):
+            run_step(i)
+        s1.record()
+        torch.cuda.synchronize()
+        sustained = {"ms_per_step": s0.elapsed_time(s1) / n_sus, "steps": n_sus}
 
     # ---- algorithmic work per launch (one layer)
     T = n + Lc
-    eb = 2 if cfg.dtype == "bf16" else 4
+    eb = 2 if is_bf16 else 4
     visible_pairs = Lc * n_kept + sum(min(Lc, (i // L_B + 1) * L_B) for i in range(Lc))
     attn_flops = 4.0 * visible_pairs * D * N
     F_in = n_seg * H
@@ -315,49 +435,57 @@ def main():
         "score": {"ms": avg["score"], "min_ms": mn["score"], "GB/s": bytes_score / avg["score"] / 1e6,
                   "frac_hbm": bytes_score / avg["score"] / 1e6 / PEAK_HBM_GBS,
                   "TFLOP/s": 2.0 * T * F_in * M / avg["score"] / 1e9},
-        "select": {"ms": avg["select"], "min_ms": mn["select"], "GB/s": bytes_select / avg["select"] / 1e6},
+        "select": {"ms": avg["select"], "min_ms": mn["select"],
+                   "GB/s": bytes_select * (1 if n_layers == 1 or shared else n_layers) / max(avg["select"], 1e-9) / 1e6,
+                   "empty_kernel_ms": empty_ms, "x_empty_kernel": avg["select"] / empty_ms if empty_ms > 0 else None,
+                   "note": select_note},
         "compact": {"ms": avg["compact"], "min_ms": mn["compact"], "GB/s": bytes_compact / avg["compact"] / 1e6,
-                    "frac_hbm": bytes_compact / avg["compact"] / 1e6 / PEAK_HBM_GBS},
+                    "frac_hbm": bytes_compact / avg["compact"] / 1e6 / PEAK_HBM_GBS, "salient": a.structure},
         "attention": {"ms": avg["attention"], "min_ms": mn["attention"], "TFLOP/s": attn_tflops,
                       "frac_mfma": attn_tflops / PEAK_BF16_TFLOPS},
     }
-    # The kernels of a step run back to back (no gaps in the kernel trace), so the attention launch's duration inside
-    # the timed whole steps is the step time minus the three short stages.  It is a few percent longer than the
-    # duration between the stage events above, where the event records leave the chip short rests; the roofline
-    # figure uses the in-step duration, which is also what the rocprofv3 average over the same command shows.
-    # (a multi-layer step selects for up to 32 layers in one launch, one workgroup per layer; with shared indices it
-    # scores and selects once for all layers).  Never report less than the duration between the stage events.
-    shared = a.shared_index and n_layers > 1
-    score_share = avg["score"] / n_layers if shared else avg["score"]
-    select_share = avg["select"] / n_layers if shared else avg["select"] * ((n_layers + 31) // 32) / n_layers
-    attn_in_step_ms = max(ms_per_step / n_layers - (score_share + select_share + avg["compact"]), avg["attention"])
-    attn_in_step_tflops = attn_flops / (attn_in_step_ms * 1e-3) / 1e12
-    roofline = {"kernel": "chunk_attention_kernel", "bound": "mfma", "achieved": attn_in_step_tflops,
-                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": attn_in_step_tflops / PEAK_BF16_TFLOPS,
-                "traffic": MEASURED_ATTENTION_TRAFFIC_BYTES.get((a.workload, L_B == Lc)),
-                "flops_per_launch": attn_flops, "avg_launch_ms": attn_in_step_ms,
-                "avg_launch_ms_between_stage_events": avg["attention"]}
+    # cross-check of the event-measured attention duration: the kernels of a step run back to back, so inside the
+    # plain timed steps (no stage events) the attention launch lasts the step minus the three short stages
+    n_scoring = 1 if (shared or n_layers == 1) else n_layers
+    inferred = (ms_per_step - avg["score"] * n_scoring - avg["select"]) / n_layers - avg["compact"]
+    traffic = ATTENTION_TRAFFIC.get((a.workload, L_B == Lc))
+    roofline = {"kernel": "chunk_attention_kernel", "bound": "mfma", "achieved": attn_tflops,
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": attn_tflops / PEAK_BF16_TFLOPS,
+                "traffic": traffic[0] if traffic else None,
+                "traffic_source": (traffic[1] + " (separate rocprofv3 --pmc run, not re-measured here)") if traffic else None,
+                "flops_per_launch": attn_flops, "avg_launch_ms": avg["attention"], "launches_timed": len(attn_ms),
+                "how": "hipEventRecord before and after the attention launch inside the step entry point, on the launch "
+                       "stream, over %d whole steps" % a.steps,
+                "ms_per_step_with_stage_events": ms_with_events,
+                "step_minus_short_stages_ms": inferred}
 
-    # ---- CPU baseline: the oracle as it stands, bounded sample of the same workload
-    cpu = None
-    if not a.no_cpu_baseline and a.workload in ("C1", "C0", "C2") and not paper_head:
+    # ---- CPU leg: the oracle as it stands on a bounded sample of the same workload, timed; its outputs are also the
+    # parity reference for the device buffers of the last step that ran on input set 0 (teacher-forced like the tests:
+    # the oracle selects on the device's fp32 scores, so indices and cache must match bit for bit)
+    cpu, parity, parity_ok = None, None, True
+    if not a.no_cpu_baseline and a.workload in ("C1", "C0", "C2", "C4") and not paper_head:
         from oracle import pafu_oracle as orc
         try:
             from threadpoolctl import threadpool_info
             cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
         except Exception:
             cores = len(os.sched_getaffinity(0))
+        s0 = sets[0]
+        got_scores = s0["scores"].cpu().numpy()
         # about 10-30 s of CPU work: every query row at the Wan-1.3B layer, a strided sample above that
         n_rows = Lc if Lc * (n_kept + Lc) * N <= 1.3e9 else max(96, int(1.3e9 / ((n_kept + Lc) * N)))
         rows = np.arange(Lc) if n_rows >= Lc else np.unique(np.linspace(0, Lc - 1, n_rows).astype(np.int64))
+        # with shared indices layer 0's cache follows ANOTHER layer's scores: then the oracle is only timed, on its own
+        cpu_only = shared
         c0 = time.perf_counter()
         s_ref = orc.smlp_score(np.concatenate([d["X_cache"], d["X_chunk"]]), d["W1"], None, d["W2"], None)
         c1 = time.perf_counter()
-        ids_ref = orc.select_topk(s_ref[:n].astype(np.float32), k)
+        sel_scores = s_ref[:n].astype(np.float32) if cpu_only else got_scores[:n]
+        ids_ref = orc.select_topk(sel_scores, k, a.pinned)
         c2 = time.perf_counter()
-        Kk, Vk, _ = orc.compact_kv(d["K_cache"], d["V_cache"], s_ref[:n].astype(np.float32), ids_ref)
+        Kk, Vk, SLk = orc.compact_kv(kvq["K_cache"], kvq["V_cache"], sel_scores, ids_ref)
         c3 = time.perf_counter()
-        orc.chunk_attention(d["Q"], Kk, Vk, d["K_chunk"], d["V_chunk"], block_len=L_B, rows=rows)
+        O_ref = orc.chunk_attention(kvq["Q"], Kk, Vk, kvq["K_chunk"], kvq["V_chunk"], block_len=L_B, rows=rows)
         c4 = time.perf_counter()
         attn_full_ms = (c4 - c3) * 1e3 * (Lc / len(rows))
         total = (c1 - c0) * 1e3 + (c2 - c1) * 1e3 + (c3 - c2) * 1e3 + attn_full_ms
@@ -367,23 +495,50 @@ def main():
                          "scaled by %d/%d%s" % (len(rows), Lc, Lc, len(rows), "; x30 layers" if n_layers > 1 else ""),
                "stages_ms": {"score": (c1 - c0) * 1e3, "select": (c2 - c1) * 1e3, "compact": (c3 - c2) * 1e3,
                              "attention_extrapolated": attn_full_ms}}
+        if not cpu_only:
+            f32 = lambda t_: t_.float().cpu().numpy()
+            got_ids = s0["ids"].cpu().numpy()[:n_kept]
+            got_O = f32(s0["O"]).astype(np.float64)[rows]
+            cache_mism = 2 * int((f32(s0["K_out"])[:n_kept] != Kk).sum() + (f32(s0["V_out"])[:n_kept] != Vk).sum()) \
+                + 4 * int((s0["SL_out"].cpu().numpy()[:n_kept] != SLk).sum())
+            parity = {
+                "score_max_abs": float(np.abs(got_scores - s_ref).max()),
+                "id_mismatches": int((got_ids != ids_ref).sum()),
+                "cache_byte_mismatches": cache_mism,
+                "attn_max_abs": float(np.abs(got_O - O_ref).max()),
+                "attn_rel_fro": float(np.linalg.norm(got_O - O_ref) / np.linalg.norm(O_ref)),
+                "attn_rows_checked": int(len(rows)),
+                "how": "buffers of input set 0 after the last step (layer 0 of a multi-layer step); the oracle "
+                       "selects on the device's fp32 scores",
+                "tolerances": dict(TOL, id_mismatches=0, cache_byte_mismatches=0),
+            }
+            parity_ok = (parity["score_max_abs"] < TOL["score_max_abs"] and parity["id_mismatches"] == 0
+                         and parity["cache_byte_mismatches"] == 0 and parity["attn_max_abs"] < TOL["attn_max_abs"]
+                         and parity["attn_rel_fro"] < TOL["attn_rel_fro"])
+            parity["ok"] = bool(parity_ok)
 
     out = {
-        "metric": "ms per AR chunk step (score+select+compact+attn), MFMA util and HBM GB/s",
+        "metric": METRIC,
         "value": ms_per_step, "unit": "ms", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+        "dtype": "bf16" if is_bf16 else "f32", "data": "synthetic",
         "config": {"workload": "%s: %d layer(s), %d heads x %d, cache %d tokens, chunk %d queries, budget %d, "
                                "S-MLP %d->%d->%d, L_B=%d, salient=%s" % (a.workload, n_layers, N, D, n, Lc, k, F_in, M,
                                                                           12 if paper_head else cfg.n_out, L_B,
                                                                           a.structure),
                    "layers": n_layers, "input_sets": n_sets,
-                   "indices": "shared (last layer's head)" if (a.shared_index and n_layers > 1) else "per layer",
+                   "indices": "shared (last layer's head)" if shared else "per layer",
                    "n_pinned": a.pinned},
-        "wall_ms_per_step": wall_ms, "stages": stages, "roofline": roofline, "cpu_baseline": cpu,
+        "wall_ms_per_step": wall_ms,
+        "sustained_ms_per_step": sustained["ms_per_step"] if sustained else None,
+        "sustained_steps": sustained["steps"] if sustained else None,
+        "stages": stages, "roofline": roofline, "parity": parity, "cpu_baseline": cpu,
         "input_gen_s": gen_s,
     }
     print(json.dumps(out))
+    if not parity_ok:
+        print("bench.py: parity against the oracle is out of tolerance: %s" % json.dumps(parity), file=sys.stderr)
+        sys.exit(1)
 
 
 if __name__ == "__main__":

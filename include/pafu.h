@@ -52,6 +52,9 @@ const char* pafu_strerror(int status);
 int pafu_last_hip_error(void);
 /* Library ABI version (increases when a signature changes). */
 int pafu_version(void);
+/* Enqueues an empty kernel (one wavefront, no memory access) on `stream`: the floor of what any stage can take
+ * between two events on a stream, reported next to the latency-bound selection stage. */
+int pafu_launch_probe(void* stream);
 
 /* ------------------------------------------------------------------------------------------
  * pafu_score - Salience Estimation Head (S-MLP), App. A "S-MLP"; Sec. 3.3-3.4.
@@ -139,7 +142,12 @@ int pafu_compact_kv(void* stream, const void* K, const void* V, const float* SL,
  *   Kn,Vn : [Lc, N, D] bf16, stride ld_n   O : [Lq, N, D] of out_dtype (bf16 or fp32), stride ld_o
  *   softmax_scale <= 0 means 1/sqrt(D).    D must be 64 or 128.  Lq >= 1, Lc >= 1, block_len >= 1.
  *   Query i is chunk token i (Lq <= Lc on this path).
- *   workspace : pafu_attention_workspace_bytes(...) bytes (may be 0 -> NULL allowed)
+ *   workspace : optional (NULL / 0 allowed).  With pafu_attention_workspace_bytes(Lq, N, D) bytes (16-byte aligned,
+ *               apart from every tensor of the call) a launch whose (head, 256-query tile) items would fill at most
+ *               four fifths of the GPU's compute units cuts its work into equal runs over the key axis, one per
+ *               compute unit, and merges the partial results in a second pass: the same result up to the rounding
+ *               of the softmax weights, several times faster for short chunks over a long cache.  The contents of
+ *               the workspace need not be initialised and are not kept.  Results do not depend on timing either way.
  */
 size_t pafu_attention_workspace_bytes(int Lq, int N, int D);
 int pafu_chunk_attention(void* stream, const void* Q, int Lq, const void* Kc, const void* Vc, int n_kept,
@@ -223,8 +231,16 @@ typedef struct pafu_step_args {
   void* O;             /* [Lc, N, D] out */
   void* workspace; size_t workspace_bytes; /* >= pafu_step_workspace_bytes(args) */
   int n_pinned;        /* frame sink: cached tokens [0, n_pinned) are never evicted (0 = none) */
+  /* Optional timing hooks (host handles, hipEvent_t passed as void*, each NULL = not recorded): recorded on the
+   * step's stream before scoring [0], after scoring [1], after selection [2], after compaction [3] and after
+   * attention [4] (ROLLOUT: the append follows [4]).  In the multi-layer steps, whose stages are reordered across
+   * layers, [0]/[1] bracket the layer's scoring and [3]/[4] its attention launch; [2] is not recorded there. */
+  void* stage_events[5];
 } pafu_step_args;
 
+/* Workspace of a step = the scoring part (only when n_out > 1; required) followed by the attention part (optional:
+ * see pafu_chunk_attention).  pafu_step_workspace_bytes returns the size of both; a workspace that only covers the
+ * scoring part is accepted and the attention launch then runs without its equal-run split. */
 size_t pafu_step_workspace_bytes(const pafu_step_args* args /* host */);
 int pafu_step(void* stream, const pafu_step_args* args /* host */);
 /* The same step for n_layers independent layers (args[l] is layer l's arguments), enqueued on one stream.

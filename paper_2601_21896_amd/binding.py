@@ -20,7 +20,7 @@ PAFU_ACT_SILU, PAFU_ACT_GELU_ERF = 0, 1
 PAFU_MODE_SINGLE, PAFU_MODE_ROLLOUT = 0, 1
 
 SYMBOLS = (
-    "pafu_strerror", "pafu_last_hip_error", "pafu_version",
+    "pafu_strerror", "pafu_last_hip_error", "pafu_version", "pafu_launch_probe",
     "pafu_score_workspace_bytes", "pafu_score", "pafu_score_static",
     "pafu_select_workspace_bytes", "pafu_select_topk", "pafu_select_topk_pinned",
     "pafu_compact_kv",
@@ -53,6 +53,7 @@ class pafu_step_args(Structure):
         ("scores", c_void_p), ("ids", c_void_p), ("K_out", c_void_p), ("V_out", c_void_p),
         ("SL_out", c_void_p), ("O", c_void_p), ("workspace", c_void_p), ("workspace_bytes", c_size_t),
         ("n_pinned", c_int),
+        ("stage_events", c_void_p * 5),
     ]
 
 
@@ -71,6 +72,8 @@ def _lib():
         lib.pafu_strerror.argtypes = [c_int]
         lib.pafu_last_hip_error.restype = c_int
         lib.pafu_version.restype = c_int
+        lib.pafu_launch_probe.restype = c_int
+        lib.pafu_launch_probe.argtypes = [c_void_p]
         lib.pafu_score_workspace_bytes.restype = c_size_t
         lib.pafu_score_workspace_bytes.argtypes = [c_int]
         lib.pafu_score.restype = c_int
@@ -161,6 +164,29 @@ def pafu_version() -> int:
 
 def pafu_strerror(status: int) -> str:
     return _lib().pafu_strerror(status).decode()
+
+
+def pafu_launch_probe(stream=None):
+    _check(_lib().pafu_launch_probe(_stream(stream)), "pafu_launch_probe")
+
+
+def set_stage_events(args: "pafu_step_args", events):
+    """Attaches up to five timing events (torch.cuda.Event objects that have been recorded once, or raw hipEvent_t
+    handles, or None) to a step's argument struct."""
+    keep = []
+    for i in range(5):
+        e = events[i] if i < len(events) else None
+        if e is None:
+            args.stage_events[i] = None
+        elif isinstance(e, int):
+            args.stage_events[i] = e
+        else:
+            handle = e.cuda_event
+            if not handle:
+                raise ValueError("record the event once before attaching it (its handle is created lazily)")
+            args.stage_events[i] = handle
+            keep.append(e)
+    args._keep_events = keep
 
 
 def pafu_score_workspace_bytes(M: int) -> int:

@@ -12,7 +12,29 @@ int record_hip_error(hipError_t e) {
   g_last_hip_error = static_cast<int>(e);
   return PAFU_ERR_HIP;
 }
+int compute_units() {
+  static std::mutex mu;
+  static int cached[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  std::lock_guard<std::mutex> lock(mu);
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    cached[dev] = n;
+  }
+  return cached[dev];
+}
 namespace {
+
+__global__ void probe_kernel() {}
+
+// Optional timing hook of a step.
+int record_stage(hipStream_t st, const pafu_step_args* a, int i) {
+  if (a->stage_events[i] == nullptr) return PAFU_OK;
+  const hipError_t e = hipEventRecord(static_cast<hipEvent_t>(a->stage_events[i]), st);
+  return e == hipSuccess ? PAFU_OK : record_hip_error(e);
+}
 
 int dtype_bytes(int dtype) { return dtype == PAFU_BF16 ? 2 : (dtype == PAFU_F32 ? 4 : 0); }
 
@@ -184,7 +206,24 @@ int check_layers_alias(const pafu_step_args* args, int n_layers, int index_layer
   return PAFU_OK;
 }
 
+// The optional workspace of the attention calls: aligned, and apart from every tensor of the call.
+int check_attention_ws(const void* ws, size_t ws_bytes, const void* Q, int Lq, const void* Kc, const void* Vc, int n_c,
+                       const void* Kn, const void* Vn, int Lc, long long ld_q, long long ld_c, long long ld_n,
+                       long long ld_o, const void* O, int out_dtype) {
+  if (ws == nullptr || ws_bytes == 0) return PAFU_OK;
+  if (!aligned16(ws)) return PAFU_ERR_ALIGN;
+  if (overlaps(ws, ws_bytes, Q, (size_t)Lq * ld_q * 2) || overlaps(ws, ws_bytes, Kn, (size_t)Lc * ld_n * 2) ||
+      overlaps(ws, ws_bytes, Vn, (size_t)Lc * ld_n * 2) || overlaps(ws, ws_bytes, O, (size_t)Lq * ld_o * dtype_bytes(out_dtype)) ||
+      (n_c > 0 && (overlaps(ws, ws_bytes, Kc, (size_t)n_c * ld_c * 2) || overlaps(ws, ws_bytes, Vc, (size_t)n_c * ld_c * 2))))
+    return PAFU_ERR_ALIAS;
+  return PAFU_OK;
+}
+
 size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+// The part of a step's workspace that the scoring needs (the rest, if present, serves the attention launch).
+size_t step_score_workspace(const pafu_step_args* a) {
+  return a->n_out > 1 ? align_up(pafu_score_workspace_bytes(a->M)) : 0;
+}
 
 // Validates a whole step without enqueuing anything.
 int check_step(const pafu_step_args* a) {
@@ -193,9 +232,10 @@ int check_step(const pafu_step_args* a) {
   if (a->n < 0 || a->k < 0 || a->Lc < 1 || a->N < 1 || a->D < 1 || a->n_pinned < 0) return PAFU_ERR_SHAPE;
   const int n_kept = a->k < a->n ? a->k : a->n;
   const bool single = a->mode == PAFU_MODE_SINGLE;
-  if (a->workspace_bytes < pafu_step_workspace_bytes(a) || (a->workspace == nullptr && a->workspace_bytes > 0))
+  if (a->workspace_bytes < step_score_workspace(a) || (a->workspace == nullptr && a->workspace_bytes > 0))
     return PAFU_ERR_WORKSPACE;
-  if (pafu_step_workspace_bytes(a) > 0 && a->workspace == nullptr) return PAFU_ERR_WORKSPACE;
+  if (step_score_workspace(a) > 0 && a->workspace == nullptr) return PAFU_ERR_WORKSPACE;
+  if (!aligned16(a->workspace)) return PAFU_ERR_ALIGN;
   int rc;
   float* chunk_scores = single ? (a->scores ? a->scores + a->n : nullptr) : (a->SL_out ? a->SL_out + n_kept : nullptr);
   if (!chunk_scores) return PAFU_ERR_NULL;
@@ -230,7 +270,8 @@ int check_step(const pafu_step_args* a) {
 int enqueue_scores(hipStream_t st, const pafu_step_args* a) {
   const int n_kept = a->k < a->n ? a->k : a->n;
   const bool single = a->mode == PAFU_MODE_SINGLE;
-  int rc;
+  int rc = record_stage(st, a, 0);
+  if (rc) return rc;
   float* chunk_scores = single ? a->scores + a->n : a->SL_out + n_kept;
   if (single && a->n > 0) {
     // cache and chunk features that sit back to back are scored in one launch
@@ -257,12 +298,24 @@ int enqueue_scores(hipStream_t st, const pafu_step_args* a) {
                       a->W1, a->b1, a->W2, a->b2, a->M, a->n_out, a->act, chunk_scores, a->workspace);
     if (rc) return rc;
   }
-  return PAFU_OK;
+  return record_stage(st, a, 1);
+}
+
+// The part of a layer's workspace that the attention launch may use: what lies behind the scoring part.
+struct WsPart {
+  void* p;
+  size_t bytes;
+};
+WsPart attention_ws(const pafu_step_args* a, bool scoring) {
+  const size_t used = scoring ? step_score_workspace(a) : 0;
+  if (a->workspace == nullptr || a->workspace_bytes <= used) return WsPart{nullptr, 0};
+  return WsPart{static_cast<char*>(a->workspace) + used, a->workspace_bytes - used};
 }
 
 // The cache part of a step for one layer: compact K/V (and the score list when sel_scores is given) to `ids`,
 // attend over retained + chunk, and in ROLLOUT append the chunk's K/V behind the retained rows.
-int enqueue_kv(hipStream_t st, const pafu_step_args* a, const int* ids, const float* sel_scores, float* SL_out) {
+int enqueue_kv(hipStream_t st, const pafu_step_args* a, const int* ids, const float* sel_scores, float* SL_out,
+               void* attn_ws, size_t attn_ws_bytes) {
   const int n_kept = a->k < a->n ? a->k : a->n;
   const float scale = a->softmax_scale > 0.f ? a->softmax_scale : 1.0f / sqrtf((float)a->D);
   int rc;
@@ -271,8 +324,13 @@ int enqueue_kv(hipStream_t st, const pafu_step_args* a, const int* ids, const fl
                         a->K_out, a->V_out, SL_out, a->ld_out * 2);
     if (rc) return rc;
   }
+  rc = record_stage(st, a, 3);
+  if (rc) return rc;
   rc = launch_attention(st, a->Q, a->Lc, a->K_out, a->V_out, n_kept, a->K_chunk, a->V_chunk, a->Lc, a->N, a->D,
-                        a->ld_chunk, a->ld_out, a->ld_chunk, a->ld_o, a->block_len, scale, a->O, a->out_dtype);
+                        a->ld_chunk, a->ld_out, a->ld_chunk, a->ld_o, a->block_len, scale, a->O, a->out_dtype, attn_ws,
+                        attn_ws_bytes);
+  if (rc) return rc;
+  rc = record_stage(st, a, 4);
   if (rc) return rc;
   if (a->mode != PAFU_MODE_SINGLE) {
     char* ko = static_cast<char*>(a->K_out) + (long long)n_kept * a->ld_out * 2;
@@ -292,7 +350,10 @@ int enqueue_step(hipStream_t st, const pafu_step_args* a) {
     rc = launch_select(st, sel_scores, a->n, a->k, a->n_pinned, a->ids, nullptr, nullptr);
     if (rc) return rc;
   }
-  return enqueue_kv(st, a, a->ids, sel_scores, a->SL_out);
+  rc = record_stage(st, a, 2);
+  if (rc) return rc;
+  const WsPart ws = attention_ws(a, true);
+  return enqueue_kv(st, a, a->ids, sel_scores, a->SL_out, ws.p, ws.bytes);
 }
 
 // Validates the cache part of a layer that takes its indices from another layer.
@@ -337,7 +398,12 @@ const char* pafu_strerror(int status) {
 }
 
 int pafu_last_hip_error(void) { return g_last_hip_error; }
-int pafu_version(void) { return 2; }
+int pafu_version(void) { return 3; }
+
+int pafu_launch_probe(void* stream) {
+  hipLaunchKernelGGL(probe_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream));
+  return check_launch();
+}
 
 size_t pafu_score_workspace_bytes(int M) { return M > 0 ? ((size_t)M + 1) * sizeof(float) : 0; }
 
@@ -393,20 +459,22 @@ int pafu_compact_kv(void* stream, const void* K, const void* V, const float* SL,
 }
 
 size_t pafu_attention_workspace_bytes(int Lq, int N, int D) {
-  (void)Lq; (void)N; (void)D;
-  return 0;
+  (void)Lq; (void)N;
+  return (D == 64 || D == 128) ? attention_workspace_bytes(D) : 0;
 }
 
 int pafu_chunk_attention(void* stream, const void* Q, int Lq, const void* Kc, const void* Vc, int n_kept, const void* Kn,
                          const void* Vn, int Lc, int N, int D, long long ld_q, long long ld_c, long long ld_n,
                          long long ld_o, int block_len, float softmax_scale, void* O, int out_dtype, void* workspace,
                          size_t workspace_bytes) {
-  (void)workspace; (void)workspace_bytes;
   int rc = check_attention(Q, Lq, Kc, Vc, n_kept, Kn, Vn, Lc, N, D, ld_q, ld_c, ld_n, ld_o, block_len, O, out_dtype);
+  if (rc) return rc;
+  rc = check_attention_ws(workspace, workspace_bytes, Q, Lq, Kc, Vc, n_kept, Kn, Vn, Lc, ld_q, ld_c, ld_n, ld_o, O,
+                          out_dtype);
   if (rc) return rc;
   const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)D);
   return launch_attention(static_cast<hipStream_t>(stream), Q, Lq, Kc, Vc, n_kept, Kn, Vn, Lc, N, D, ld_q, ld_c, ld_n,
-                          ld_o, block_len, scale, O, out_dtype);
+                          ld_o, block_len, scale, O, out_dtype, workspace, workspace_bytes);
 }
 
 int pafu_chunk_attention_gather(void* stream, const void* Q, int Lq, const void* K_cache, const void* V_cache,
@@ -414,7 +482,6 @@ int pafu_chunk_attention_gather(void* stream, const void* Q, int Lq, const void*
                                 int D, long long ld_q, long long ld_c, long long ld_n, long long ld_o, int block_len,
                                 float softmax_scale, void* O, int out_dtype, void* workspace,
                                 size_t workspace_bytes) {
-  (void)workspace; (void)workspace_bytes;
   if (n_cache < 0 || n_kept < 0 || n_kept > n_cache) return PAFU_ERR_SHAPE;
   if (n_kept > 0 && !ids) return PAFU_ERR_NULL;
   if (!aligned16(ids)) return PAFU_ERR_ALIGN;
@@ -425,9 +492,12 @@ int pafu_chunk_attention_gather(void* stream, const void* Q, int Lq, const void*
   int rc = check_attention(Q, Lq, K_cache, V_cache, n_cache, Kn, Vn, Lc, N, D, ld_q, ld_c, ld_n, ld_o, block_len, O,
                            out_dtype);
   if (rc) return rc;
+  rc = check_attention_ws(workspace, workspace_bytes, Q, Lq, K_cache, V_cache, n_cache, Kn, Vn, Lc, ld_q, ld_c, ld_n,
+                          ld_o, O, out_dtype);
+  if (rc) return rc;
   const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)D);
   return launch_attention(static_cast<hipStream_t>(stream), Q, Lq, K_cache, V_cache, n_kept, Kn, Vn, Lc, N, D, ld_q,
-                          ld_c, ld_n, ld_o, block_len, scale, O, out_dtype, ids, n_cache);
+                          ld_c, ld_n, ld_o, block_len, scale, O, out_dtype, workspace, workspace_bytes, ids, n_cache);
 }
 
 size_t pafu_sse_workspace_bytes(int L, int N) { return L > 0 && N > 0 ? sse_workspace_bytes(L, N) : 0; }
@@ -459,7 +529,7 @@ int pafu_sse_score(void* stream, const void* Q, const void* K, int L, int N, int
 
 size_t pafu_step_workspace_bytes(const pafu_step_args* a) {
   if (!a) return 0;
-  return a->n_out > 1 ? align_up(pafu_score_workspace_bytes(a->M)) : 0;
+  return step_score_workspace(a) + attention_workspace_bytes(a->D);
 }
 
 int pafu_step(void* stream, const pafu_step_args* args) {
@@ -502,7 +572,8 @@ int pafu_step_layers(void* stream, const pafu_step_args* args, int n_layers) {
   }
   for (int l = 0; l < n_layers; ++l) {
     const pafu_step_args* a = &args[l];
-    int rc = enqueue_kv(st, a, a->ids, a->mode == PAFU_MODE_SINGLE ? a->scores : a->SL_in, a->SL_out);
+    const WsPart ws = attention_ws(a, true);
+    int rc = enqueue_kv(st, a, a->ids, a->mode == PAFU_MODE_SINGLE ? a->scores : a->SL_in, a->SL_out, ws.p, ws.bytes);
     if (rc) return rc;
   }
   return PAFU_OK;
@@ -533,7 +604,11 @@ int pafu_step_layers_shared(void* stream, const pafu_step_args* args, int n_laye
   }
   for (int l = 0; l < n_layers; ++l) {
     const bool is_idx = l == index_layer;
-    rc = enqueue_kv(st, &args[l], idx->ids, is_idx ? sel_scores : nullptr, is_idx ? idx->SL_out : nullptr);
+    // a layer without a workspace of its own borrows the index layer's (the layers run one after the other)
+    WsPart ws = attention_ws(&args[l], is_idx);
+    if (ws.p == nullptr) ws = attention_ws(idx, true);
+    rc = enqueue_kv(st, &args[l], idx->ids, is_idx ? sel_scores : nullptr, is_idx ? idx->SL_out : nullptr, ws.p,
+                    ws.bytes);
     if (rc) return rc;
   }
   return PAFU_OK;

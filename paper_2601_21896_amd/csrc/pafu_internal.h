@@ -67,9 +67,13 @@ int launch_score_static(hipStream_t st, const void* x0, const void* x1, const vo
 size_t sse_workspace_bytes(int L, int N);
 int launch_sse(hipStream_t st, const void* Q, const void* K, int L, int N, int D, long long ld_q, long long ld_k,
                int block_len, float scale, float* out, void* workspace);
+// workspace (may be null): with attention_workspace_bytes(D) bytes the launch may cut its work into equal runs.
+size_t attention_workspace_bytes(int D);
 int launch_attention(hipStream_t st, const void* Q, int Lq, const void* Kc, const void* Vc, int n_kept,
                      const void* Kn, const void* Vn, int Lc, int N, int D, long long ld_q, long long ld_c,
                      long long ld_n, long long ld_o, int block_len, float scale, void* O, int out_dtype,
-                     const int* ids = nullptr, int n_cache = 0);
+                     void* workspace, size_t workspace_bytes, const int* ids = nullptr, int n_cache = 0);
+// Compute units of the current GPU (cached per device; 256 if the query fails).
+int compute_units();
 
 }  // namespace pafu

@@ -39,3 +39,19 @@ def attn_errors(got, want):
 ATTN_MAX_ABS = 2e-2
 ATTN_REL_FRO = 5e-3
 SCORE_MAX_ABS = 1e-3
+
+
+def attention_workspace(D):
+    """Device buffer with which the attention launch may cut its work into equal runs."""
+    from paper_2601_21896_amd import binding as B
+    return torch.empty(B.pafu_attention_workspace_bytes(1, 1, D), dtype=torch.uint8, device=DEV)
+
+
+def step_workspace(args):
+    """Device buffer of pafu_step_workspace_bytes(args) bytes, attached to the argument struct."""
+    from paper_2601_21896_amd import binding as B
+    ws = torch.empty(max(B.pafu_step_workspace_bytes(args), 16), dtype=torch.uint8, device=DEV)
+    args.workspace = ws.data_ptr()
+    args.workspace_bytes = ws.numel()
+    args._keep_ws = ws
+    return ws

@@ -6,7 +6,7 @@ import torch
 from oracle import pafu_oracle as orc
 from paper_2601_21896_amd import binding as B
 from paper_2601_21896_amd import workloads as wl
-from tests.gpu_util import ATTN_MAX_ABS, ATTN_REL_FRO, DEV, attn_errors, dev, host
+from tests.gpu_util import ATTN_MAX_ABS, ATTN_REL_FRO, DEV, attention_workspace, attn_errors, dev, host
 
 pytestmark = pytest.mark.gpu
 
@@ -22,7 +22,7 @@ def _inputs(n, Lc, N, D, seed, q_gain=1.0):
     return Q, Kc, Vc, Kn, Vn
 
 
-def _run(Q, Kc, Vc, Kn, Vn, L_B, out_dtype=torch.bfloat16, Lq=None):
+def _run(Q, Kc, Vc, Kn, Vn, L_B, out_dtype=torch.bfloat16, Lq=None, ws=None):
     Lq = Q.shape[0] if Lq is None else Lq
     N, D = Q.shape[1], Q.shape[2]
     n = Kc.shape[0]
@@ -30,7 +30,7 @@ def _run(Q, Kc, Vc, Kn, Vn, L_B, out_dtype=torch.bfloat16, Lq=None):
     dQ = dev(Q[:Lq], "bf16")
     dKc = dev(Kc, "bf16") if n else None
     dVc = dev(Vc, "bf16") if n else None
-    B.pafu_chunk_attention(dQ, dKc, dVc, n, dev(Kn, "bf16"), dev(Vn, "bf16"), L_B, O[:Lq])
+    B.pafu_chunk_attention(dQ, dKc, dVc, n, dev(Kn, "bf16"), dev(Vn, "bf16"), L_B, O[:Lq], workspace=ws)
     torch.cuda.synchronize()
     assert torch.all(O[Lq:] == 55.0)
     return host(O[:Lq])
@@ -67,6 +67,42 @@ def test_attention_peaked_softmax_and_fp32_output():
         got = _run(Q, Kc, Vc, Kn, Vn, 64, out_dtype=odt)
         max_abs, rel = attn_errors(got, want)
         assert max_abs < ATTN_MAX_ABS and rel < ATTN_REL_FRO, (odt, max_abs, rel)
+
+
+# With a workspace the launch cuts the flattened (head, query tile, key tiles) list into equal runs, one per CU, and
+# merges the partial results of the query tiles that several workgroups worked on.  These shapes are long enough for
+# that path to be taken (a few query tiles, hundreds of key tiles each), so a query tile is shared by many runs.
+@pytest.mark.parametrize("n,Lc,N,D,L_B,odt,q_gain", [
+    (16000, 600, 4, 128, 600, torch.bfloat16, 1.0),   # 12 items of 130 units each over 256 runs
+    (9000, 1500, 3, 128, 500, torch.bfloat16, 1.0),   # block mask: the items have different lengths
+    (9000, 1500, 3, 128, 500, torch.float32, 8.0),    # ... peaked softmax, fp32 output
+    (20000, 300, 5, 64, 300, torch.bfloat16, 1.0),    # head dim 64
+    (0, 9000, 2, 128, 1, torch.bfloat16, 1.0),        # no cache, strictly causal inside the chunk
+    (12345, 777, 3, 128, 100, torch.bfloat16, 1.0),   # ragged everything
+])
+def test_attention_equal_runs_match_oracle(n, Lc, N, D, L_B, odt, q_gain):
+    Q, Kc, Vc, Kn, Vn = _inputs(n, Lc, N, D, seed=n + Lc + N, q_gain=q_gain)
+    ws = attention_workspace(D)
+    got = _run(Q, Kc, Vc, Kn, Vn, L_B, out_dtype=odt, ws=ws)
+    want = orc.chunk_attention(Q, Kc, Vc, Kn, Vn, block_len=L_B)
+    max_abs, rel = attn_errors(got, want)
+    assert max_abs < ATTN_MAX_ABS and rel < ATTN_REL_FRO, (max_abs, rel)
+    # the same launch without the workspace (one workgroup per query tile) agrees to the rounding of the bf16
+    # softmax weights (taken relative to different running maxima), and a second launch with the workspace (now
+    # holding the first one's partial results) gives the same bits as the first
+    plain = _run(Q, Kc, Vc, Kn, Vn, L_B, out_dtype=odt)
+    assert np.abs(plain - got).max() < ATTN_MAX_ABS * max(1.0, np.abs(want).max())
+    again = _run(Q, Kc, Vc, Kn, Vn, L_B, out_dtype=odt, ws=ws)
+    assert np.array_equal(got, again)
+
+
+def test_attention_workspace_too_small_falls_back_to_whole_query_tiles():
+    n, Lc, N, D = 16000, 600, 4, 128
+    Q, Kc, Vc, Kn, Vn = _inputs(n, Lc, N, D, seed=3)
+    small = torch.empty(4096, dtype=torch.uint8, device=DEV)
+    got = _run(Q, Kc, Vc, Kn, Vn, Lc, ws=small)
+    plain = _run(Q, Kc, Vc, Kn, Vn, Lc)
+    assert np.array_equal(got, plain)
 
 
 def test_attention_large_key_offset_and_fewer_queries():
@@ -130,6 +166,24 @@ def test_gather_attention_matches_oracle_and_the_compacted_path(n_cache, n_kept,
     # same arithmetic in the same order as the plain kernel on the compacted cache: identical bits
     plain = _run(Q, Kc[ids], Vc[ids], Kn, Vn, L_B)
     assert np.array_equal(got, plain)
+
+
+def test_gather_attention_with_equal_runs():
+    n_cache, n_kept, Lc, N, D, L_B = 30000, 17000, 600, 4, 128, 200
+    Q, Kc, Vc, Kn, Vn = _inputs(n_cache, Lc, N, D, seed=41)
+    ids = np.sort(np.random.default_rng(4).permutation(n_cache)[:n_kept]).astype(np.int32)
+    ws = attention_workspace(D)
+    O = torch.full((Lc + 2, N, D), 55.0, device=DEV, dtype=torch.bfloat16)
+    B.pafu_chunk_attention_gather(dev(Q, "bf16"), dev(Kc, "bf16"), dev(Vc, "bf16"), torch.from_numpy(ids).to(DEV), n_kept,
+                                  dev(Kn, "bf16"), dev(Vn, "bf16"), L_B, O[:Lc], workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.all(O[Lc:] == 55.0)
+    want = orc.chunk_attention(Q, Kc[ids], Vc[ids], Kn, Vn, block_len=L_B)
+    max_abs, rel = attn_errors(host(O[:Lc]), want)
+    assert max_abs < ATTN_MAX_ABS and rel < ATTN_REL_FRO, (max_abs, rel)
+    # the plain kernel on the compacted cache with the same workspace cuts the work the same way: identical bits
+    plain = _run(Q, Kc[ids], Vc[ids], Kn, Vn, L_B, ws=ws)
+    assert np.array_equal(host(O[:Lc]), plain)
 
 
 def test_gather_attention_clamps_out_of_range_ids():

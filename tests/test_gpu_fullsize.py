@@ -16,7 +16,7 @@ import torch
 from oracle import pafu_oracle as orc
 from paper_2601_21896_amd import binding as B
 from paper_2601_21896_amd import workloads as wl
-from tests.gpu_util import ATTN_MAX_ABS, ATTN_REL_FRO, DEV, SCORE_MAX_ABS, attn_errors, dev, host
+from tests.gpu_util import ATTN_MAX_ABS, ATTN_REL_FRO, DEV, SCORE_MAX_ABS, attn_errors, dev, host, step_workspace
 
 pytestmark = pytest.mark.gpu
 
@@ -29,7 +29,7 @@ def _sample_rows(cfg):
     return np.array(sorted(rows))
 
 
-def _run_full(cfg, L_B, score_rows=None, structure="uniform", all_rows=False):
+def _run_full(cfg, L_B, score_rows=None, structure="uniform", all_rows=False, workspace=True):
     d = wl.make_layer_inputs(cfg, structure=structure)
     n, Lc, N, D, k = cfg.n, cfg.Lc, cfg.N, cfg.D, cfg.k
     X = dev(np.concatenate([d["X_cache"], d["X_chunk"]]), "bf16")
@@ -43,6 +43,8 @@ def _run_full(cfg, L_B, score_rows=None, structure="uniform", all_rows=False):
                             dev(d["W2"]), None, dev(d["K_cache"], "bf16"), dev(d["V_cache"], "bf16"), None,
                             dev(d["Q"], "bf16"), dev(d["K_chunk"], "bf16"), dev(d["V_chunk"], "bf16"), scores, ids,
                             K_out, V_out, SL_out, O)
+    if workspace:                                          # with it the attention launch cuts its work into equal runs
+        step_workspace(args)
     B.pafu_step(args)
     torch.cuda.synchronize()
     got_s = host(scores)
@@ -69,6 +71,17 @@ def test_c1_full_step_paper_block_length():
 def test_c1_full_step_frame_blocks_and_coherent_salience():
     # L_B = one frame: the block mask is live in the last 3 x 1560 keys
     _run_full(wl.C1, wl.C1.frame_tokens, structure="coherent", all_rows=True)
+
+
+def test_c1_full_step_without_workspace():
+    # no workspace: one workgroup per (head, query tile), nothing merged
+    _run_full(wl.C1, wl.C1.Lc, workspace=False)
+
+
+def test_c1_one_frame_chunk_takes_the_equal_run_split():
+    # a one-frame chunk (1560 queries = 84 items on 256 compute units) over the full cache: with the workspace the
+    # attention launch cuts the key axis into equal runs and merges partial results
+    _run_full(wl.scaled(wl.C1, chunk_frames=1), wl.C1.frame_tokens, all_rows=True)
 
 
 def test_c4_full_step_sampled():
@@ -103,11 +116,12 @@ class _Layer:
         self.SL_out = torch.zeros(cfg.k, device=DEV)
         self.O = torch.zeros(cfg.Lc, cfg.N, cfg.D, device=DEV, dtype=torch.bfloat16)
 
-    def args(self, L_B):
+    def args(self, L_B, workspace=None):
         cfg, n = self.cfg, self.cfg.n
         return B.make_step_args(B.PAFU_MODE_SINGLE, cfg.N, cfg.D, n, cfg.Lc, cfg.k, L_B, self.X[:n], self.X[n:],
                                 self.W1, None, self.W2, None, self.K, self.V, None, self.Q, self.Kn, self.Vn,
-                                self.scores, self.ids, self.K_out, self.V_out, self.SL_out, self.O)
+                                self.scores, self.ids, self.K_out, self.V_out, self.SL_out, self.O,
+                                workspace=workspace)
 
 
 @pytest.fixture(scope="module")
@@ -124,7 +138,8 @@ def test_c2_thirty_layers_independent_indices(c2_layers):
     rows = _sample_rows(cfg)
     for L in c2_layers:
         L.outputs()
-    B.pafu_step_layers([L.args(L_B) for L in c2_layers])
+    ws = torch.empty(B.pafu_attention_workspace_bytes(cfg.Lc, cfg.N, cfg.D), dtype=torch.uint8, device=DEV)
+    B.pafu_step_layers([L.args(L_B, ws) for L in c2_layers])      # the layers may share one workspace
     torch.cuda.synchronize()
     seen = set()
     for l, L in enumerate(c2_layers):
@@ -151,7 +166,9 @@ def test_c2_thirty_layers_shared_indices(c2_layers):
     idx = len(c2_layers) - 1                   # the head reads the final layer (Sec. 3.3)
     for L in c2_layers:
         L.outputs()
-    B.pafu_step_layers_shared([L.args(L_B) for L in c2_layers], idx)
+    ws = torch.empty(B.pafu_attention_workspace_bytes(cfg.Lc, cfg.N, cfg.D), dtype=torch.uint8, device=DEV)
+    # only the index layer brings a workspace: the others borrow it
+    B.pafu_step_layers_shared([L.args(L_B, ws if l == idx else None) for l, L in enumerate(c2_layers)], idx)
     torch.cuda.synchronize()
     d = c2_layers[idx].d
     got_s = host(c2_layers[idx].scores)
@@ -186,6 +203,7 @@ def _rollout_full(k, n_chunks):
     st = orc.RolloutState(N, D, np.float32)
     ids = torch.empty(k, dtype=torch.int32, device=DEV)
     O = torch.empty(Lc, N, D, device=DEV, dtype=torch.bfloat16)
+    ws = torch.empty(B.pafu_attention_workspace_bytes(Lc, N, D), dtype=torch.uint8, device=DEV)
     n, cur, sizes, evictions = 0, 0, [], 0
     for t in range(n_chunks):
         c = wl.make_chunk_inputs(cfg, t)
@@ -194,7 +212,7 @@ def _rollout_full(k, n_chunks):
         args = B.make_step_args(B.PAFU_MODE_ROLLOUT, N, D, n, Lc, k, L_B, None, dev(c["X_chunk"], "bf16"), dW1, None,
                                 dW2, None, src["K"], src["V"], src["SL"], dev(c["Q"], "bf16"),
                                 dev(c["K_chunk"], "bf16"), dev(c["V_chunk"], "bf16"), None, ids, dst["K"], dst["V"],
-                                dst["SL"], O)
+                                dst["SL"], O, workspace=ws)
         B.pafu_step(args)
         torch.cuda.synchronize()
         s_chunk = host(dst["SL"][n_kept:n_kept + Lc])
