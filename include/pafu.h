@@ -52,6 +52,10 @@ const char* pafu_strerror(int status);
 int pafu_last_hip_error(void);
 /* Library ABI version (increases when a signature changes). */
 int pafu_version(void);
+/* 0 for the library as shipped.  Non-zero: a study build whose attention kernel was compiled with ingredients of its
+ * inner loop taken out (to measure what they cost); such a build computes wrong results and is only ever loaded by
+ * name, by the measurements recorded under profiles/. */
+int pafu_study_build(void);
 /* Enqueues an empty kernel (one wavefront, no memory access) on `stream`: the floor of what any stage can take
  * between two events on a stream, reported next to the latency-bound selection stage. */
 int pafu_launch_probe(void* stream);

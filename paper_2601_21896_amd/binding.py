@@ -20,7 +20,7 @@ PAFU_ACT_SILU, PAFU_ACT_GELU_ERF = 0, 1
 PAFU_MODE_SINGLE, PAFU_MODE_ROLLOUT = 0, 1
 
 SYMBOLS = (
-    "pafu_strerror", "pafu_last_hip_error", "pafu_version", "pafu_launch_probe",
+    "pafu_strerror", "pafu_last_hip_error", "pafu_version", "pafu_study_build", "pafu_launch_probe",
     "pafu_score_workspace_bytes", "pafu_score", "pafu_score_static",
     "pafu_select_workspace_bytes", "pafu_select_topk", "pafu_select_topk_pinned",
     "pafu_compact_kv",
@@ -72,6 +72,7 @@ def _lib():
         lib.pafu_strerror.argtypes = [c_int]
         lib.pafu_last_hip_error.restype = c_int
         lib.pafu_version.restype = c_int
+        lib.pafu_study_build.restype = c_int
         lib.pafu_launch_probe.restype = c_int
         lib.pafu_launch_probe.argtypes = [c_void_p]
         lib.pafu_score_workspace_bytes.restype = c_size_t
@@ -164,6 +165,10 @@ def pafu_version() -> int:
 
 def pafu_strerror(status: int) -> str:
     return _lib().pafu_strerror(status).decode()
+
+
+def pafu_study_build() -> int:
+    return _lib().pafu_study_build()
 
 
 def pafu_launch_probe(stream=None):

@@ -35,9 +35,13 @@ def _run(cmd):
     return out
 
 
-def build(verbose: bool = False, extra_flags=()) -> str:
-    """Compiles every translation unit and links libpafu.so; always recompiles."""
-    obj_dir = os.path.join(HERE, "_build")
+def build(verbose: bool = False, extra_flags=(), out: str = "") -> str:
+    """Compiles every translation unit and links libpafu.so; always recompiles.
+
+    `out` names another library file next to libpafu.so (study builds with extra -D flags, loaded by name through
+    bench.py --library); its objects go to a directory of their own so that the product build is left alone."""
+    LIB = os.path.join(HERE, out) if out else globals()["LIB"]
+    obj_dir = os.path.join(HERE, "_build" + ("_" + os.path.splitext(out)[0] if out else ""))
     os.makedirs(obj_dir, exist_ok=True)
     cc = hipcc()
     objs = [os.path.join(obj_dir, s.replace(".hip", ".o")) for s in SOURCES]
@@ -54,4 +58,10 @@ def build(verbose: bool = False, extra_flags=()) -> str:
 
 
 if __name__ == "__main__":
-    print(build(verbose=True, extra_flags=sys.argv[1:]))
+    argv = sys.argv[1:]
+    out_name = ""
+    if "--out" in argv:
+        i = argv.index("--out")
+        out_name = argv[i + 1]
+        del argv[i:i + 2]
+    print(build(verbose=True, extra_flags=argv, out=out_name))

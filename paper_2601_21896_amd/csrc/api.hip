@@ -400,6 +400,8 @@ const char* pafu_strerror(int status) {
 int pafu_last_hip_error(void) { return g_last_hip_error; }
 int pafu_version(void) { return 3; }
 
+int pafu_study_build(void) { return attention_study_build(); }
+
 int pafu_launch_probe(void* stream) {
   hipLaunchKernelGGL(probe_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream));
   return check_launch();

@@ -74,6 +74,16 @@ constexpr int kAtIdStages = 8;        // ids ring depth (gather variant): a tile
 constexpr int kAtIdLead = 3;
 constexpr int kAtXcds = 8;            // accelerator dies, each with its own L2
 constexpr float kAtLazyLog2 = 8.0f;   // raise the running maximum only when it grows by more than 2^8
+// Study builds only (never the shipped library, which is built without the macro): PAFU_ATTN_ABLATE is a bit mask that
+// takes ingredients out of the inner loop so that what they cost can be measured on the same shapes and data; the
+// results of such a build are meaningless.  pafu_study_build() returns the mask.
+//   1: no global -> LDS tile copies inside the loop (the ring keeps the tiles of the prologue)
+//   2: no softmax arithmetic (P = the upper halves of S, one byte-permute per pair; sums and maxima untouched)
+#ifndef PAFU_ATTN_ABLATE
+#define PAFU_ATTN_ABLATE 0
+#endif
+constexpr bool kAblateLoads = (PAFU_ATTN_ABLATE & 1) != 0;
+constexpr bool kAblateSoftmax = (PAFU_ATTN_ABLATE & 2) != 0;
 constexpr float kAtNoMax = -1.0e30f;  // running maximum before the first visible key (finite on purpose)
 constexpr int kAtMaxRuns = 256;       // most workgroups the unit list is ever cut into (one per CU)
 
@@ -186,7 +196,19 @@ __device__ __forceinline__ void attn_step(const f32x16 (&s_cur)[2], f32x16 (&s_n
       asm volatile("" : "+v"(o[db]));
     }
     // ---- vector pipe slice
-    if (i < 4) {  // row maximum over a quarter of the tile's keys
+    if (kAblateSoftmax) {
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        if ((u * NSLOT) / 16 == i) {
+          const int kb = u >> 3, r = 2 * (u & 7);
+          p_cur[2 * kb + (r >> 3)][(r & 7) >> 1] = __builtin_amdgcn_perm(
+              __float_as_uint(s_cur[kb][r + 1]), __float_as_uint(s_cur[kb][r]), 0x07060302u);
+        }
+      }
+      alpha = 1.f;
+      grow = false;
+      psum = 1.f;
+    } else if (i < 4) {  // row maximum over a quarter of the tile's keys
       const int kb = i >> 1, r0 = 8 * (i & 1);
       float t = i ? mx : s_cur[0][0];
       asm volatile("" : "+v"(t));
@@ -518,7 +540,7 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnArgs
 #pragma unroll 1
       for (int t = 0; t < 2 * n_iter; ++t) {
         if (GATHER) issue_ids(tb + t + kAtStages + kAtIdLead);
-        issue_tiles(t + kAtStages);
+        if (!kAblateLoads) issue_tiles(t + kAtStages);
         wait_vmcnt<(kAtStages - 2) * (2 * LPT + (GATHER ? 1 : 0))>();
         __builtin_amdgcn_s_barrier();
       }
@@ -566,7 +588,7 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnArgs
         {
           const int t = 2 * T;
           if (GATHER) issue_ids(tb + t + kAtStages + kAtIdLead);
-          issue_tiles(t + kAtStages);
+          if (!kAblateLoads) issue_tiles(t + kAtStages);
           if ((tb + t + 1) * kAtTileKeys > lim_min) attn_mask(s_a, (tb + t) * kAtTileKeys, lim, g);
           attn_step<D>(s_a, s_b, p_b, p_a, o, qf, msc, l_run, k_addr(t + 1), v_addr(t > 0 ? t - 1 : 0), kx2, vx2, sc);
           wait_vmcnt<(kAtStages - 2) * (2 * LPT + (GATHER ? 1 : 0))>();
@@ -575,7 +597,7 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnArgs
         {
           const int t = 2 * T + 1;
           if (GATHER) issue_ids(tb + t + kAtStages + kAtIdLead);
-          issue_tiles(t + kAtStages);
+          if (!kAblateLoads) issue_tiles(t + kAtStages);
           if ((tb + t + 1) * kAtTileKeys > lim_min) attn_mask(s_b, (tb + t) * kAtTileKeys, lim, g);
           attn_step<D>(s_b, s_a, p_a, p_b, o, qf, msc, l_run, k_addr(T + 1 < n_iter ? t + 1 : t), v_addr(t - 1), kx2, vx2, sc);
           wait_vmcnt<(kAtStages - 2) * (2 * LPT + (GATHER ? 1 : 0))>();
@@ -729,6 +751,8 @@ int launch_dims(hipStream_t st, const AttnArgs& a, int D, bool f32) {
 }
 
 }  // namespace
+
+int attention_study_build() { return PAFU_ATTN_ABLATE; }
 
 // Bytes of workspace with which every launch can cut its work into equal runs: two partial-result slots for each of
 // at most kAtMaxRuns workgroups.

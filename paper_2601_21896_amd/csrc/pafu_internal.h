@@ -69,6 +69,7 @@ int launch_sse(hipStream_t st, const void* Q, const void* K, int L, int N, int D
                int block_len, float scale, float* out, void* workspace);
 // workspace (may be null): with attention_workspace_bytes(D) bytes the launch may cut its work into equal runs.
 size_t attention_workspace_bytes(int D);
+int attention_study_build();  // 0 in the shipped library; the ablation mask of a study build
 int launch_attention(hipStream_t st, const void* Q, int Lq, const void* Kc, const void* Vc, int n_kept,
                      const void* Kn, const void* Vn, int Lc, int N, int D, long long ld_q, long long ld_c,
                      long long ld_n, long long ld_o, int block_len, float scale, void* O, int out_dtype,

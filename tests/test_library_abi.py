@@ -24,6 +24,7 @@ def test_every_declared_symbol_is_exported():
     for name in names:
         assert getattr(lib, name) is not None
     assert binding.pafu_version() >= 1
+    assert binding.pafu_study_build() == 0          # the in-tree library is the product, not a study build
     assert binding.pafu_strerror(0) == "ok"
     assert "NULL" in binding.pafu_strerror(-1)
 
