@@ -58,6 +58,10 @@ def parse():
     ap.add_argument("--sustained-s", type=float, default=1.0,
                     help="length of the extra back-to-back run behind sustained_ms_per_step (0 = skip)")
     ap.add_argument("--chunk-frames", type=int, default=0, help="ATTN only: frames per chunk (default 3)")
+    ap.add_argument("--no-attention-workspace", action="store_true",
+                    help="ATTN only: call pafu_chunk_attention without a workspace (never cuts its work into equal runs)")
+    ap.add_argument("--shape", default="C1", choices=["C1", "C4"],
+                    help="ATTN only: heads, frame size and budget of the Wan-1.3B (C1) or Wan-14B (C4) layer")
     ap.add_argument("--data", default="normal", choices=["normal", "zeros"],
                     help="ATTN only: N(0,1) tensors (default) or all-zero tensors (same instructions, no operand toggling)")
     ap.add_argument("--library", default="", help="load this build of libpafu.so instead of the in-tree default")
@@ -114,9 +118,9 @@ def sse(a, torch, np, B, wl):
 
 
 def attention_only(a, torch, np, B, wl):
-    """The attention stage alone at the Wan-1.3B layer shape (retained cache 16380 + chunk), launched back to back:
-    the workload of the kernel studies under profiles/ (N(0,1) or all-zero tensors, any build of the library)."""
-    cfg = wl.C1
+    """The attention stage alone at the Wan-1.3B (or Wan-14B) layer shape (retained cache + chunk), launched back to
+    back: the workload of the kernel studies under profiles/ (N(0,1) or all-zero tensors, any build of the library)."""
+    cfg = wl.CONFIGS[a.shape]
     dev = "cuda:0"
     N, D, k = cfg.N, cfg.D, cfg.k
     Lc = (a.chunk_frames or cfg.chunk_frames) * cfg.frame_tokens
@@ -134,7 +138,7 @@ def attention_only(a, torch, np, B, wl):
 
     def run(i):
         Q, Kc, Vc, Kn, Vn = sets[i % len(sets)]
-        B.pafu_chunk_attention(Q, Kc, Vc, k, Kn, Vn, L_B, O, workspace=ws)
+        B.pafu_chunk_attention(Q, Kc, Vc, k, Kn, Vn, L_B, O, workspace=None if a.no_attention_workspace else ws)
     for i in range(a.warmup):
         run(i)
     torch.cuda.synchronize()

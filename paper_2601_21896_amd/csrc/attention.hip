@@ -79,11 +79,13 @@ constexpr float kAtLazyLog2 = 8.0f;   // raise the running maximum only when it 
 // results of such a build are meaningless.  pafu_study_build() returns the mask.
 //   1: no global -> LDS tile copies inside the loop (the ring keeps the tiles of the prologue)
 //   2: no softmax arithmetic (P = the upper halves of S, one byte-permute per pair; sums and maxima untouched)
+//   4: equal runs whenever a workspace is given, also when the items fill the chip (results stay correct)
 #ifndef PAFU_ATTN_ABLATE
 #define PAFU_ATTN_ABLATE 0
 #endif
 constexpr bool kAblateLoads = (PAFU_ATTN_ABLATE & 1) != 0;
 constexpr bool kAblateSoftmax = (PAFU_ATTN_ABLATE & 2) != 0;
+constexpr bool kStudySplitAlways = (PAFU_ATTN_ABLATE & 4) != 0;
 constexpr float kAtNoMax = -1.0e30f;  // running maximum before the first visible key (finite on purpose)
 constexpr int kAtMaxRuns = 256;       // most workgroups the unit list is ever cut into (one per CU)
 
@@ -799,7 +801,7 @@ int launch_attention(hipStream_t st, const void* Q, int Lq, const void* Kc, cons
   // heads and thrash its L2.  They need the workspace, and runs of at least a few units each.
   int cus = compute_units();
   if (cus > kAtMaxRuns) cus = kAtMaxRuns;
-  const bool uneven = items * 5 <= (long long)cus * 4;
+  const bool uneven = items * 5 <= (long long)cus * 4 || kStudySplitAlways;
   w.split = 0;
   w.n_wg = (int)items;
   w.part_o = nullptr;
