@@ -12,7 +12,7 @@ only library steps.  There is no tiling, no online softmax and no fusion.
 Inputs are whatever values the device path sees, widened exactly: a bf16 tensor
 arrives here as float32/float64 values that are exactly representable in bf16.
 
-Pins (tests/test_oracle_*.py): every function below is pinned by closed forms,
+Pins (tests/test_oracle_*.py): every function below is pinned by closed forms, value tables of the number format,
 brute force on tiny inputs, invariants, or reduction to an independent library
 routine.  The paper prints no worked numeric example for any stage, so no pin
 is a printed value.
@@ -39,6 +39,9 @@ __all__ = [
     "step_single_shared",
     "rollout_step_shared",
     "sse_score",
+    "quantise_e4m3",
+    "dequantise_e4m3",
+    "rollout_step_fp8",
 ]
 
 
@@ -262,6 +265,84 @@ def rollout_step(state: RolloutState, X_chunk, W1, b1, W2, b2, Q, K_chunk, V_chu
     state.V = np.concatenate([Vk, np.asarray(V_chunk, dtype=Vk.dtype)], axis=0)
     state.SL = np.concatenate([SLk, s32]).astype(np.float32)
     return dict(s_chunk=s_chunk, ids=ids, O=O)
+
+
+# --------------------------------------------------------------------------------------
+# 8-bit storage of the K/V cache (beyond the paper: App. A states no storage precision)
+# --------------------------------------------------------------------------------------
+E4M3_MAX = 448.0          # largest finite magnitude: 1.75 * 2^8
+E4M3_MIN_NORMAL = 2.0 ** -6
+E4M3_SUBNORMAL_STEP = 2.0 ** -9
+
+
+def quantise_e4m3(x, scale_log2: int = 0) -> np.ndarray:
+    """Codes of x / 2^scale_log2 in the 8-bit floating-point format E4M3 (1 sign, 4 exponent bits with bias 7,
+    3 mantissa bits; no infinities; exponent 15 with mantissa 7 is NaN; the "fn" variant of the OCP 8-bit
+    floating-point specification).  Reading taken for the cache (the paper gives none): one power-of-two scale per
+    tensor chosen by the caller, round to nearest with ties to the even mantissa, magnitudes beyond 448 saturate
+    to 448, NaN stays NaN, the sign of zero is kept.
+
+    The value grid: for exponent field E >= 1, 2^(E-7) (1 + M/8); for E = 0, 2^-6 (M/8).  Rounding is done by
+    scaling to the grid's local step and rounding to the nearest integer (ties to even), which is exact in
+    float64 for every finite input.
+
+    returns uint8 codes, same shape as x.
+    """
+    v = np.asarray(x, dtype=np.float64) / (2.0 ** int(scale_log2))
+    sign = np.signbit(v)
+    a = np.minimum(np.abs(v), E4M3_MAX)
+    nan = np.isnan(v)
+    a = np.where(nan, 0.0, a)
+    # local step of the grid: 2^(floor(log2 a) - 3) for normals, 2^-9 below the smallest normal
+    with np.errstate(divide="ignore"):
+        ex = np.floor(np.log2(np.where(a > 0, a, 1.0)))
+    ex = np.maximum(ex, -6.0)
+    step = 2.0 ** (ex - 3.0)
+    q = np.rint(a / step) * step              # np.rint rounds halves to even; a / step is exact (power-of-two step)
+    # q may have moved up to the next binade (mantissa 8/8): recompute exponent and mantissa from q itself
+    with np.errstate(divide="ignore"):
+        eq = np.floor(np.log2(np.where(q > 0, q, 1.0)))
+    normal = q >= E4M3_MIN_NORMAL
+    E = np.where(normal, eq + 7.0, 0.0)
+    M = np.where(normal, q / 2.0 ** eq * 8.0 - 8.0, q / E4M3_SUBNORMAL_STEP)
+    code = (E.astype(np.int64) << 3) | M.astype(np.int64)
+    code = np.where(nan, 0x7F, code)
+    code = code | (sign.astype(np.int64) << 7)
+    return code.astype(np.uint8)
+
+
+def dequantise_e4m3(codes, scale_log2: int = 0) -> np.ndarray:
+    """Values of E4M3 codes times 2^scale_log2, float64 (exact)."""
+    c = np.asarray(codes, dtype=np.uint8).astype(np.int64)
+    E = (c >> 3) & 0xF
+    M = c & 7
+    mag = np.where(E > 0, 2.0 ** (E - 7.0) * (1.0 + M / 8.0), E4M3_MIN_NORMAL * (M / 8.0))
+    mag = np.where((E == 15) & (M == 7), np.nan, mag)
+    return np.where((c >> 7) == 1, -mag, mag) * (2.0 ** int(scale_log2))
+
+
+def rollout_step_fp8(state: RolloutState, X_chunk, W1, b1, W2, b2, Q, K_chunk, V_chunk, k: int, block_len: int,
+                     k_scale_log2: int, v_scale_log2: int, act: str = "silu", forced_chunk_scores_f32=None,
+                     n_pinned: int = 0, rows=None):
+    """rollout_step with the cache held as E4M3 codes (state.K / state.V are uint8 arrays).
+
+    The chunk's K/V are quantised when they enter the step, so the chunk's queries attend over exactly the values
+    that later steps will find in the cache; selection and compaction move codes; attention runs on the
+    dequantised values.  returns dict(s_chunk f64, ids, O, K_codes, V_codes of the chunk); mutates state.
+    """
+    s_chunk = smlp_score(X_chunk, W1, b1, W2, b2, act)
+    s32 = (s_chunk.astype(np.float32) if forced_chunk_scores_f32 is None
+           else np.asarray(forced_chunk_scores_f32, np.float32))
+    ids = select_topk(state.SL, k, n_pinned)
+    Kk, Vk, SLk = compact_kv(state.K, state.V, state.SL, ids)
+    Kq = quantise_e4m3(K_chunk, k_scale_log2)
+    Vq = quantise_e4m3(V_chunk, v_scale_log2)
+    O = chunk_attention(Q, dequantise_e4m3(Kk, k_scale_log2), dequantise_e4m3(Vk, v_scale_log2),
+                        dequantise_e4m3(Kq, k_scale_log2), dequantise_e4m3(Vq, v_scale_log2), block_len, rows=rows)
+    state.K = np.concatenate([Kk, Kq], axis=0)
+    state.V = np.concatenate([Vk, Vq], axis=0)
+    state.SL = np.concatenate([SLk, s32]).astype(np.float32)
+    return dict(s_chunk=s_chunk, ids=ids, O=O, K_codes=Kq, V_codes=Vq)
 
 
 # --------------------------------------------------------------------------------------
