@@ -28,6 +28,7 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 METRIC = "ms per AR chunk step (score+select+compact+attn), MFMA util and HBM GB/s"
+FP8_SCALES = (-5, -6)         # log2 of the K and V scales of the 8-bit cache: |K| <= 14, |V| <= 7 representable
 TOL = {"score_max_abs": 1e-3, "attn_max_abs": 2e-2, "attn_rel_fro": 5e-3}   # the benchmark spec's tolerances
 
 # HBM bytes per attention launch from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE, scaled by a copy kernel): a figure
@@ -64,6 +65,8 @@ def parse():
                     help="ATTN only: heads, frame size and budget of the Wan-1.3B (C1) or Wan-14B (C4) layer")
     ap.add_argument("--data", default="normal", choices=["normal", "zeros"],
                     help="ATTN only: N(0,1) tensors (default) or all-zero tensors (same instructions, no operand toggling)")
+    ap.add_argument("--kv", default="bf16", choices=["bf16", "fp8"],
+                    help="storage of the K/V cache: bf16, or 8-bit E4M3 codes with power-of-two scales 2^-5 (K), 2^-6 (V)")
     ap.add_argument("--library", default="", help="load this build of libpafu.so instead of the in-tree default")
     return ap.parse_args()
 
@@ -133,12 +136,23 @@ def attention_only(a, torch, np, B, wl):
             return torch.zeros(rows, N, D, device=dev, dtype=torch.bfloat16)
         return torch.randn(rows, N, D, device=dev, generator=g).to(torch.bfloat16)
     sets = [(tensor(Lc), tensor(k), tensor(k), tensor(Lc), tensor(Lc)) for _ in range(max(1, a.sets))]
+    if a.kv == "fp8":       # both key segments as codes
+        def codes(Kt, Vt):
+            Kq = torch.empty(Kt.shape[0], N * D, dtype=torch.uint8, device=dev)
+            Vq = torch.empty_like(Kq)
+            B.pafu_quantize_kv(Kt, Vt, FP8_SCALES[0], FP8_SCALES[1], Kq, Vq)
+            return Kq, Vq
+        sets = [(Q,) + codes(Kc, Vc) + codes(Kn, Vn) for Q, Kc, Vc, Kn, Vn in sets]
     O = torch.empty(Lc, N, D, device=dev, dtype=torch.bfloat16)
     ws = torch.empty(B.pafu_attention_workspace_bytes(Lc, N, D), dtype=torch.uint8, device=dev)
 
     def run(i):
         Q, Kc, Vc, Kn, Vn = sets[i % len(sets)]
-        B.pafu_chunk_attention(Q, Kc, Vc, k, Kn, Vn, L_B, O, workspace=None if a.no_attention_workspace else ws)
+        w = None if a.no_attention_workspace else ws
+        if a.kv == "fp8":
+            B.pafu_chunk_attention_fp8(Q, Kc, Vc, k, Kn, Vn, L_B, FP8_SCALES[0], FP8_SCALES[1], O, workspace=w)
+        else:
+            B.pafu_chunk_attention(Q, Kc, Vc, k, Kn, Vn, L_B, O, workspace=w)
     for i in range(a.warmup):
         run(i)
     torch.cuda.synchronize()
@@ -157,7 +171,8 @@ def attention_only(a, torch, np, B, wl):
         "warmup": a.warmup, "ms_per_step": ms, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic (%s)" % ("N(0,1)" if a.data == "normal" else "all zeros"),
         "config": {"workload": "ATTN: %d queries x (%d retained + %d chunk keys), %d heads x %d, L_B=%d" %
-                               (Lc, k, Lc, N, D, L_B), "library": a.library or "in-tree libpafu.so"},
+                               (Lc, k, Lc, N, D, L_B), "library": a.library or "in-tree libpafu.so",
+                   "kv_storage": a.kv},
         "median_ms": float(np.median(t)), "min_ms": float(t.min()),
         "roofline": {"kernel": "chunk_attention_kernel", "bound": "mfma", "achieved": flops / ms / 1e9,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": flops / ms / 1e9 / PEAK_BF16_TFLOPS,
@@ -183,8 +198,16 @@ def rollout(a, torch, np, B, wl):
     for c in range(4):      # chunk inputs cycle through 4 generated sets (fresh K/V/features per chunk seed)
         ci = wl.make_chunk_inputs(cfg, c)
         pool.append(dict(X=t(ci["X_chunk"], True), Q=t(ci["Q"], True), K=t(ci["K_chunk"], True), V=t(ci["V_chunk"], True)))
-    slabs = [dict(K=torch.zeros(cap, N, D, device=dev, dtype=bf), V=torch.zeros(cap, N, D, device=dev, dtype=bf),
-                  SL=torch.zeros(cap, device=dev)) for _ in range(2)]
+    fp8 = a.kv == "fp8"
+    kvb = 1 if fp8 else 2
+    if fp8:
+        slabs = [dict(K=torch.zeros(cap, N * D, device=dev, dtype=torch.uint8),
+                      V=torch.zeros(cap, N * D, device=dev, dtype=torch.uint8), SL=torch.zeros(cap, device=dev))
+                 for _ in range(2)]
+    else:
+        slabs = [dict(K=torch.zeros(cap, N, D, device=dev, dtype=bf), V=torch.zeros(cap, N, D, device=dev, dtype=bf),
+                      SL=torch.zeros(cap, device=dev)) for _ in range(2)]
+    kv_args = dict(kv_dtype=B.PAFU_FP8_E4M3, k_scale_log2=FP8_SCALES[0], v_scale_log2=FP8_SCALES[1]) if fp8 else {}
     ids = torch.empty(max(k, 1), dtype=torch.int32, device=dev)
     O = torch.empty(Lc, N, D, device=dev, dtype=bf)
     ws = torch.empty(B.pafu_attention_workspace_bytes(Lc, N, D), dtype=torch.uint8, device=dev)
@@ -198,7 +221,7 @@ def rollout(a, torch, np, B, wl):
             src, dst = slabs[cur], slabs[1 - cur]
             args = B.make_step_args(B.PAFU_MODE_ROLLOUT, N, D, n, Lc, k, Lc, None, c["X"], W1, None, W2, None, src["K"],
                                     src["V"], src["SL"], c["Q"], c["K"], c["V"], None, ids, dst["K"], dst["V"],
-                                    dst["SL"], O, n_pinned=a.pinned, workspace=ws)
+                                    dst["SL"], O, n_pinned=a.pinned, workspace=ws, **kv_args)
             sev = new_events(torch, 5)
             B.set_stage_events(args, sev)
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -217,17 +240,18 @@ def rollout(a, torch, np, B, wl):
     n_kept = min(k, n_steady - Lc)
     flops = 4.0 * Lc * (n_kept + Lc) * D * N
     attn_ms = float(np.mean(st[:, 3]))
-    peak_cache = 2 * (cap * N * D * 2 * 2 + cap * 4)
-    bytes_compact = 2 * (2 * n_kept * N * D * 2) + 3 * n_kept * 4
+    peak_cache = 2 * (cap * N * D * kvb * 2 + cap * 4)
+    bytes_compact = 2 * (2 * n_kept * N * D * kvb) + 3 * n_kept * 4
     out = {
         "metric": METRIC, "value": float(np.median(steady)), "unit": "ms",
         "n_gpus": 1, "steps": len(steady), "warmup": n_chunks + 5, "ms_per_step": float(np.median(steady)),
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "C3: %d-chunk rollout, 12 heads x 128, chunk %d queries, budget %d tokens, steady cache "
-                               "%d tokens, S-MLP %d->%d->1" % (n_chunks, Lc, k, n_steady, H, M)},
+                               "%d tokens, S-MLP %d->%d->1" % (n_chunks, Lc, k, n_steady, H, M), "kv_storage": a.kv},
         "min_ms": float(np.min(steady)), "first_steps_ms": [float(x) for x in times[:5]], "cache_sizes_first_steps": sizes[:6],
         "peak_cache_bytes": peak_cache,
         "stages": {s: {"ms": float(np.mean(st[:, j])), "min_ms": float(np.min(st[:, j]))} for j, s in enumerate(stage_names)},
+        "compact_bytes": bytes_compact,
         "compact_GB/s": bytes_compact / float(np.mean(st[:, 2])) / 1e6 if n_kept else None,
         "roofline": {"kernel": "chunk_attention_kernel", "bound": "mfma", "achieved": flops / attn_ms / 1e9,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": flops / attn_ms / 1e9 / PEAK_BF16_TFLOPS,
@@ -311,10 +335,13 @@ def main():
                 torch.cat([torch.roll(X[:n], 733, 0), torch.roll(X[n:], 733, 0)])]
         return tuple(t[:n] for t in segs), tuple(t[n:] for t in segs)
     n_sets = max(1, a.sets) if n_layers == 1 else 1
+    fp8 = a.kv == "fp8"
+    kvb = 1 if fp8 else 2
+    kv_args = dict(kv_dtype=B.PAFU_FP8_E4M3, k_scale_log2=FP8_SCALES[0], v_scale_log2=FP8_SCALES[1]) if fp8 else {}
     sets = []
     for s in range(n_sets * n_layers):
         if s == 0:
-            cur = base
+            cur = dict(base)
         else:
             sh = 977 * s
             cur = dict(X=torch.cat([torch.roll(base["X"][:n], sh, 0), torch.roll(base["X"][n:], sh, 0)]),
@@ -322,9 +349,16 @@ def main():
                        Q=torch.roll(base["Q"], sh, 0), Kn=torch.roll(base["Kn"], sh, 0),
                        Vn=torch.roll(base["Vn"], sh, 0))
         cur.update(scores=torch.empty(n + Lc, device=dev), ids=torch.empty(max(n_kept, 1), dtype=torch.int32, device=dev),
-                   K_out=torch.empty(max(n_kept, 1), N, D, device=dev, dtype=bf),
-                   V_out=torch.empty(max(n_kept, 1), N, D, device=dev, dtype=bf),
                    SL_out=torch.empty(max(n_kept, 1), device=dev), O=torch.empty(Lc, N, D, device=dev, dtype=bf))
+        if fp8:     # the cache arrives as codes; the output slab also takes the quantised chunk rows
+            Kq = torch.empty(n, N * D, dtype=torch.uint8, device=dev)
+            Vq = torch.empty_like(Kq)
+            B.pafu_quantize_kv(cur["K"], cur["V"], FP8_SCALES[0], FP8_SCALES[1], Kq, Vq)
+            cur.update(K=Kq, V=Vq, K_out=torch.empty(n_kept + Lc, N * D, device=dev, dtype=torch.uint8),
+                       V_out=torch.empty(n_kept + Lc, N * D, device=dev, dtype=torch.uint8))
+        else:
+            cur.update(K_out=torch.empty(max(n_kept, 1), N, D, device=dev, dtype=bf),
+                       V_out=torch.empty(max(n_kept, 1), N, D, device=dev, dtype=bf))
         cur["x_cache"], cur["x_chunk"] = feature_segments(cur["X"])
         cur["x_all"] = tuple(torch.cat([c_, n_]) for c_, n_ in zip(cur["x_cache"], cur["x_chunk"])) if paper_head \
             else (cur["X"],)
@@ -335,7 +369,7 @@ def main():
         cur["args"] = B.make_step_args(B.PAFU_MODE_SINGLE, N, D, n, Lc, k, L_B, cur["x_cache"], cur["x_chunk"], W1, b1,
                                        W2, b2, cur["K"], cur["V"], None, cur["Q"], cur["Kn"], cur["Vn"], cur["scores"],
                                        cur["ids"], cur["K_out"], cur["V_out"], cur["SL_out"], cur["O"],
-                                       workspace=cur["ws"], n_pinned=a.pinned)
+                                       workspace=cur["ws"], n_pinned=a.pinned, **kv_args)
         sets.append(cur)
     torch.cuda.synchronize()
     gen_s = time.time() - t0
@@ -433,7 +467,7 @@ def main():
     F_in = n_seg * H
     bytes_score = T * F_in * eb + M * F_in * eb + T * 4
     bytes_select = n * 4 + n_kept * 4
-    bytes_compact = 2 * (2 * n_kept * N * D * 2) + 2 * n_kept * 4 + n_kept * 4
+    bytes_compact = 2 * (2 * n_kept * N * D * kvb) + 2 * n_kept * 4 + n_kept * 4
     attn_tflops = attn_flops / (avg["attention"] * 1e-3) / 1e12
     stages = {
         "score": {"ms": avg["score"], "min_ms": mn["score"], "GB/s": bytes_score / avg["score"] / 1e6,
@@ -444,7 +478,9 @@ def main():
                    "empty_kernel_ms": empty_ms, "x_empty_kernel": avg["select"] / empty_ms if empty_ms > 0 else None,
                    "note": select_note},
         "compact": {"ms": avg["compact"], "min_ms": mn["compact"], "GB/s": bytes_compact / avg["compact"] / 1e6,
-                    "frac_hbm": bytes_compact / avg["compact"] / 1e6 / PEAK_HBM_GBS, "salient": a.structure},
+                    "frac_hbm": bytes_compact / avg["compact"] / 1e6 / PEAK_HBM_GBS, "salient": a.structure,
+                    "bytes": bytes_compact,
+                    "note": "includes quantising the chunk's K/V into the slab" if fp8 else None},
         "attention": {"ms": avg["attention"], "min_ms": mn["attention"], "TFLOP/s": attn_tflops,
                       "frac_mfma": attn_tflops / PEAK_BF16_TFLOPS},
     }
@@ -487,9 +523,21 @@ def main():
         sel_scores = s_ref[:n].astype(np.float32) if cpu_only else got_scores[:n]
         ids_ref = orc.select_topk(sel_scores, k, a.pinned)
         c2 = time.perf_counter()
-        Kk, Vk, SLk = orc.compact_kv(kvq["K_cache"], kvq["V_cache"], sel_scores, ids_ref)
-        c3 = time.perf_counter()
-        O_ref = orc.chunk_attention(kvq["Q"], Kk, Vk, kvq["K_chunk"], kvq["V_chunk"], block_len=L_B, rows=rows)
+        if fp8:     # the oracle carries codes through selection and compaction and attends on the dequantised values
+            ek, ev = FP8_SCALES
+            qz = lambda x_, e_: orc.quantise_e4m3(x_.reshape(x_.shape[0], N * D), e_)
+            dq = lambda c_, e_: orc.dequantise_e4m3(c_, e_).reshape(c_.shape[0], N, D)
+            Kc_codes, Vc_codes = qz(kvq["K_cache"], ek), qz(kvq["V_cache"], ev)
+            Kn_codes, Vn_codes = qz(kvq["K_chunk"], ek), qz(kvq["V_chunk"], ev)
+            c2 = time.perf_counter()        # (quantising the inputs is set-up, not part of the step)
+            Kk, Vk, SLk = orc.compact_kv(Kc_codes, Vc_codes, sel_scores, ids_ref)
+            c3 = time.perf_counter()
+            O_ref = orc.chunk_attention(kvq["Q"], dq(Kk, ek), dq(Vk, ev), dq(Kn_codes, ek), dq(Vn_codes, ev),
+                                        block_len=L_B, rows=rows)
+        else:
+            Kk, Vk, SLk = orc.compact_kv(kvq["K_cache"], kvq["V_cache"], sel_scores, ids_ref)
+            c3 = time.perf_counter()
+            O_ref = orc.chunk_attention(kvq["Q"], Kk, Vk, kvq["K_chunk"], kvq["V_chunk"], block_len=L_B, rows=rows)
         c4 = time.perf_counter()
         attn_full_ms = (c4 - c3) * 1e3 * (Lc / len(rows))
         total = (c1 - c0) * 1e3 + (c2 - c1) * 1e3 + (c3 - c2) * 1e3 + attn_full_ms
@@ -503,8 +551,12 @@ def main():
             f32 = lambda t_: t_.float().cpu().numpy()
             got_ids = s0["ids"].cpu().numpy()[:n_kept]
             got_O = f32(s0["O"]).astype(np.float64)[rows]
-            cache_mism = 2 * int((f32(s0["K_out"])[:n_kept] != Kk).sum() + (f32(s0["V_out"])[:n_kept] != Vk).sum()) \
-                + 4 * int((s0["SL_out"].cpu().numpy()[:n_kept] != SLk).sum())
+            if fp8:
+                gK, gV = s0["K_out"].cpu().numpy(), s0["V_out"].cpu().numpy()
+                cache_mism = int((gK != np.concatenate([Kk, Kn_codes])).sum() + (gV != np.concatenate([Vk, Vn_codes])).sum())
+            else:
+                cache_mism = 2 * int((f32(s0["K_out"])[:n_kept] != Kk).sum() + (f32(s0["V_out"])[:n_kept] != Vk).sum())
+            cache_mism += 4 * int((s0["SL_out"].cpu().numpy()[:n_kept] != SLk).sum())
             parity = {
                 "score_max_abs": float(np.abs(got_scores - s_ref).max()),
                 "id_mismatches": int((got_ids != ids_ref).sum()),
@@ -532,7 +584,7 @@ def main():
                                                                           a.structure),
                    "layers": n_layers, "input_sets": n_sets,
                    "indices": "shared (last layer's head)" if shared else "per layer",
-                   "n_pinned": a.pinned},
+                   "n_pinned": a.pinned, "kv_storage": a.kv},
         "wall_ms_per_step": wall_ms,
         "sustained_ms_per_step": sustained["ms_per_step"] if sustained else None,
         "sustained_steps": sustained["steps"] if sustained else None,

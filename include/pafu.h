@@ -42,7 +42,10 @@ typedef enum pafu_status {
   PAFU_ERR_HIP = -7        /* a HIP call failed; see pafu_last_hip_error() */
 } pafu_status;
 
-typedef enum pafu_dtype { PAFU_BF16 = 0, PAFU_F32 = 1 } pafu_dtype;
+/* PAFU_FP8_E4M3: 8-bit storage of the K/V cache (1 sign, 4 exponent bits with bias 7, 3 mantissa bits, no infinities,
+ * S.1111.111 = NaN), one byte per element, with one power-of-two scale per tensor that the caller passes as its
+ * exponent: a stored code c stands for the value c * 2^scale_log2. */
+typedef enum pafu_dtype { PAFU_BF16 = 0, PAFU_F32 = 1, PAFU_FP8_E4M3 = 2 } pafu_dtype;
 typedef enum pafu_act { PAFU_ACT_SILU = 0, PAFU_ACT_GELU_ERF = 1 } pafu_act;
 typedef enum pafu_mode { PAFU_MODE_SINGLE = 0, PAFU_MODE_ROLLOUT = 1 } pafu_mode;
 
@@ -124,7 +127,7 @@ int pafu_select_topk_pinned(void* stream, const float* scores, int n, int k, int
  *
  *   K_out[r] = K[ids[r]],  V_out[r] = V[ids[r]],  SL_out[r] = SL[ids[r]]     r in [0, count)
  * Bit copies.  Out of place (the caller ping-pongs two slabs).
- *   K, V      : [n, N, D] dtype `dtype` (2- or 4-byte elements), token stride ld_in elements
+ *   K, V      : [n, N, D] dtype `dtype` (bf16, fp32, or 8-bit codes), token stride ld_in elements
  *   SL/SL_out : [n] / [count] fp32, both NULL to skip the score list
  *   ids       : [count] int32 (device); an id outside [0, n) leaves that output row untouched
  *   K_out,V_out : [count, N, D], token stride ld_out elements
@@ -173,6 +176,29 @@ int pafu_chunk_attention_gather(void* stream, const void* Q, int Lq, const void*
                                 int N, int D, long long ld_q, long long ld_c, long long ld_n, long long ld_o,
                                 int block_len, float softmax_scale, void* O, int out_dtype, void* workspace,
                                 size_t workspace_bytes);
+
+/* ------------------------------------------------------------------------------------------
+ * 8-bit storage of the K/V cache (beyond the paper, whose App. A states no storage precision).
+ *
+ * pafu_quantize_kv: K_q[r, e] = E4M3 code of K[r, e] / 2^k_scale_log2 (round to nearest even, magnitudes beyond 448
+ * saturate, NaN stays NaN, the sign of zero is kept), likewise V.  pafu_dequantize_kv is the exact way back
+ * (code * 2^scale as bf16; exact for every code and scale).
+ *   K, V     : [rows, N, D] bf16, token stride ld_in (ld_out for dequantize) elements; N * D a multiple of 8
+ *   K_q, V_q : [rows, N * D] bytes, token stride ld_out (ld_in for dequantize) bytes, a multiple of 16
+ * pafu_compact_kv moves such rows with dtype = PAFU_FP8_E4M3 (strides in bytes).
+ *
+ * pafu_chunk_attention_fp8: pafu_chunk_attention with BOTH key segments stored as codes (ld_c, ld_n in bytes;
+ * D = 128 only).  Tiles travel as codes, half the bytes of bf16, and are widened to bf16 (times the scale, exact) in
+ * LDS before the matrix instructions read them; products, softmax and accumulation are those of the bf16 call.
+ */
+int pafu_quantize_kv(void* stream, const void* K, const void* V, long long ld_in, int rows, int N, int D,
+                     int k_scale_log2, int v_scale_log2, void* K_q, void* V_q, long long ld_out);
+int pafu_dequantize_kv(void* stream, const void* K_q, const void* V_q, long long ld_in, int rows, int N, int D,
+                       int k_scale_log2, int v_scale_log2, void* K, void* V, long long ld_out);
+int pafu_chunk_attention_fp8(void* stream, const void* Q, int Lq, const void* Kc_q, const void* Vc_q, int n_kept,
+                             const void* Kn_q, const void* Vn_q, int Lc, int N, int D, long long ld_q, long long ld_c,
+                             long long ld_n, long long ld_o, int block_len, float softmax_scale, int k_scale_log2,
+                             int v_scale_log2, void* O, int out_dtype, void* workspace, size_t workspace_bytes);
 
 /* ------------------------------------------------------------------------------------------
  * pafu_sse_score - Spatialtemporal-balanced Salience Estimation, the teacher-side score that the Salience
@@ -240,6 +266,13 @@ typedef struct pafu_step_args {
    * attention [4] (ROLLOUT: the append follows [4]).  In the multi-layer steps, whose stages are reordered across
    * layers, [0]/[1] bracket the layer's scoring and [3]/[4] its attention launch; [2] is not recorded there. */
   void* stage_events[5];
+  /* Storage of the K/V cache: PAFU_BF16 (0, the default) or PAFU_FP8_E4M3.  With the 8-bit format K_cache, V_cache,
+   * K_out and V_out hold codes (ld_cache / ld_out count bytes; D must be 128), K_chunk / V_chunk / Q stay bf16, and
+   * K_out / V_out need room for min(k, n) + Lc rows in BOTH modes: the chunk's K/V are quantised behind the retained
+   * rows before attention, so that the chunk attends over exactly the values later steps find in the cache (in
+   * ROLLOUT nothing is left to append; in SINGLE the rows are simply there).  Compaction moves codes. */
+  int kv_dtype;
+  int k_scale_log2, v_scale_log2; /* a stored code c stands for c * 2^scale_log2 (K and V each; within [-64, 64]) */
 } pafu_step_args;
 
 /* Workspace of a step = the scoring part (only when n_out > 1; required) followed by the attention part (optional:

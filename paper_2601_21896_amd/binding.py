@@ -15,7 +15,7 @@ from ctypes import (POINTER, Structure, c_char_p, c_float, c_int, c_longlong, c_
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpafu.so")
 
-PAFU_BF16, PAFU_F32 = 0, 1
+PAFU_BF16, PAFU_F32, PAFU_FP8_E4M3 = 0, 1, 2
 PAFU_ACT_SILU, PAFU_ACT_GELU_ERF = 0, 1
 PAFU_MODE_SINGLE, PAFU_MODE_ROLLOUT = 0, 1
 
@@ -25,6 +25,7 @@ SYMBOLS = (
     "pafu_select_workspace_bytes", "pafu_select_topk", "pafu_select_topk_pinned",
     "pafu_compact_kv",
     "pafu_attention_workspace_bytes", "pafu_chunk_attention", "pafu_chunk_attention_gather",
+    "pafu_quantize_kv", "pafu_dequantize_kv", "pafu_chunk_attention_fp8",
     "pafu_sse_workspace_bytes", "pafu_sse_score",
     "pafu_step_workspace_bytes", "pafu_step", "pafu_step_layers", "pafu_step_layers_shared",
 )
@@ -54,6 +55,7 @@ class pafu_step_args(Structure):
         ("SL_out", c_void_p), ("O", c_void_p), ("workspace", c_void_p), ("workspace_bytes", c_size_t),
         ("n_pinned", c_int),
         ("stage_events", c_void_p * 5),
+        ("kv_dtype", c_int), ("k_scale_log2", c_int), ("v_scale_log2", c_int),
     ]
 
 
@@ -105,6 +107,15 @@ def _lib():
                                                     c_int, c_void_p, c_void_p, c_int, c_int, c_int, c_longlong,
                                                     c_longlong, c_longlong, c_longlong, c_int, c_float, c_void_p,
                                                     c_int, c_void_p, c_size_t]
+        for f in (lib.pafu_quantize_kv, lib.pafu_dequantize_kv):
+            f.restype = c_int
+            f.argtypes = [c_void_p, c_void_p, c_void_p, c_longlong, c_int, c_int, c_int, c_int, c_int, c_void_p,
+                          c_void_p, c_longlong]
+        lib.pafu_chunk_attention_fp8.restype = c_int
+        lib.pafu_chunk_attention_fp8.argtypes = [c_void_p, c_void_p, c_int, c_void_p, c_void_p, c_int, c_void_p,
+                                                 c_void_p, c_int, c_int, c_int, c_longlong, c_longlong, c_longlong,
+                                                 c_longlong, c_int, c_float, c_int, c_int, c_void_p, c_int, c_void_p,
+                                                 c_size_t]
         lib.pafu_step_workspace_bytes.restype = c_size_t
         lib.pafu_step_workspace_bytes.argtypes = [POINTER(pafu_step_args)]
         lib.pafu_step.restype = c_int
@@ -289,9 +300,44 @@ def pafu_chunk_attention_gather(Q, K_cache, V_cache, ids, n_kept, Kn, Vn, block_
     return O
 
 
+def pafu_quantize_kv(K, V, k_scale_log2, v_scale_log2, K_q, V_q, stream=None, rows=None):
+    """K, V: [rows, N, D] bf16 -> K_q, V_q: [rows, N * D] uint8 E4M3 codes of value / 2^scale_log2."""
+    rows = K.shape[0] if rows is None else rows
+    N, D = K.shape[1], K.shape[2]
+    rc = _lib().pafu_quantize_kv(_stream(stream), _ptr(K), _ptr(V), K.stride(0), rows, N, D, k_scale_log2, v_scale_log2,
+                                 _ptr(K_q), _ptr(V_q), K_q.stride(0))
+    _check(rc, "pafu_quantize_kv")
+    return K_q, V_q
+
+
+def pafu_dequantize_kv(K_q, V_q, k_scale_log2, v_scale_log2, K, V, stream=None, rows=None):
+    """The exact way back: K, V [rows, N, D] bf16 = code * 2^scale_log2."""
+    rows = K.shape[0] if rows is None else rows
+    N, D = K.shape[1], K.shape[2]
+    rc = _lib().pafu_dequantize_kv(_stream(stream), _ptr(K_q), _ptr(V_q), K_q.stride(0), rows, N, D, k_scale_log2,
+                                   v_scale_log2, _ptr(K), _ptr(V), K.stride(0))
+    _check(rc, "pafu_dequantize_kv")
+    return K, V
+
+
+def pafu_chunk_attention_fp8(Q, Kc_q, Vc_q, n_kept, Kn_q, Vn_q, block_len, k_scale_log2, v_scale_log2, O,
+                             softmax_scale=0.0, workspace=None, stream=None):
+    """Q [Lq, N, D] bf16; Kc_q / Vc_q [n_kept, N * D] and Kn_q / Vn_q [Lc, N * D] uint8 codes."""
+    Lq, N, D = Q.shape
+    Lc = Kn_q.shape[0]
+    ld_c = Kc_q.stride(0) if Kc_q is not None else N * D
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = _lib().pafu_chunk_attention_fp8(_stream(stream), _ptr(Q), Lq, _ptr(Kc_q), _ptr(Vc_q), n_kept, _ptr(Kn_q),
+                                         _ptr(Vn_q), Lc, N, D, Q.stride(0), ld_c, Kn_q.stride(0), O.stride(0), block_len,
+                                         float(softmax_scale), k_scale_log2, v_scale_log2, _ptr(O), _dtype_code(O),
+                                         _ptr(workspace), ws_bytes)
+    _check(rc, "pafu_chunk_attention_fp8")
+    return O
+
+
 def make_step_args(mode, N, D, n, Lc, k, block_len, x_cache, x_chunk, W1, b1, W2, b2, K_cache, V_cache, SL_in, Q,
                    K_chunk, V_chunk, scores, ids, K_out, V_out, SL_out, O, act=PAFU_ACT_SILU, workspace=None,
-                   softmax_scale=0.0, n_pinned=0) -> pafu_step_args:
+                   softmax_scale=0.0, n_pinned=0, kv_dtype=PAFU_BF16, k_scale_log2=0, v_scale_log2=0) -> pafu_step_args:
     """Fills a pafu_step_args from torch tensors (x_cache / x_chunk: tensor or tuple of segments)."""
     a = pafu_step_args()
     xs_cache = x_cache if isinstance(x_cache, (tuple, list)) else ((x_cache,) if x_cache is not None else ())
@@ -302,6 +348,7 @@ def make_step_args(mode, N, D, n, Lc, k, block_len, x_cache, x_chunk, W1, b1, W2
     a.x_dtype, a.out_dtype = _dtype_code(xs_chunk[0]), _dtype_code(O)
     a.softmax_scale = float(softmax_scale)
     a.n_pinned = int(n_pinned)
+    a.kv_dtype, a.k_scale_log2, a.v_scale_log2 = int(kv_dtype), int(k_scale_log2), int(v_scale_log2)
     a.ld_x = xs_chunk[0].stride(0)
     a.ld_cache = K_cache.stride(0) if K_cache is not None else N * D
     a.ld_out = K_out.stride(0)

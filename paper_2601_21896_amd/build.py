@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpafu.so")
-SOURCES = ["api.hip", "score.hip", "select.hip", "compact.hip", "attention.hip", "sse.hip"]
+SOURCES = ["api.hip", "score.hip", "select.hip", "compact.hip", "quant.hip", "attention.hip", "sse.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

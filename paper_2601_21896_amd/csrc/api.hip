@@ -37,6 +37,9 @@ int record_stage(hipStream_t st, const pafu_step_args* a, int i) {
 }
 
 int dtype_bytes(int dtype) { return dtype == PAFU_BF16 ? 2 : (dtype == PAFU_F32 ? 4 : 0); }
+// element size of a K/V cache tensor: the 8-bit storage format is allowed there (and only there)
+int kv_dtype_bytes(int dtype) { return dtype == PAFU_FP8_E4M3 ? 1 : dtype_bytes(dtype); }
+bool scale_ok(int scale_log2) { return scale_log2 >= -64 && scale_log2 <= 64; }
 
 int check_score(const void* x0, const void* x1, const void* x2, int n_seg, int T, int Fs, long long ld_x, int x_dtype,
                 const void* W1, const float* W2, int M, int n_out, int act, const float* out, const void* ws,
@@ -67,7 +70,7 @@ int check_select(const float* scores, int n, int k, const int* out_ids) {
 int check_compact(const void* K, const void* V, const float* SL, long long ld_in, int n, const int* ids, int count,
                   int N, int D, int dtype, void* K_out, void* V_out, float* SL_out, long long ld_out) {
   if (n < 0 || count < 0 || N <= 0 || D <= 0 || count > n) return PAFU_ERR_SHAPE;
-  const int eb = dtype_bytes(dtype);
+  const int eb = kv_dtype_bytes(dtype);
   if (eb == 0) return PAFU_ERR_DTYPE;
   const long long row = (long long)N * D;
   if (ld_in < row || ld_out < row || (row * eb) % 4 != 0 || row * eb > (1ll << 30)) return PAFU_ERR_SHAPE;
@@ -88,7 +91,7 @@ int check_compact(const void* K, const void* V, const float* SL, long long ld_in
 
 int check_attention(const void* Q, int Lq, const void* Kc, const void* Vc, int n_kept, const void* Kn, const void* Vn,
                     int Lc, int N, int D, long long ld_q, long long ld_c, long long ld_n, long long ld_o,
-                    int block_len, const void* O, int out_dtype) {
+                    int block_len, const void* O, int out_dtype, int kvb = 2 /* bytes per K/V element */) {
   if (Lq < 1 || Lc < 1 || n_kept < 0 || N < 1 || block_len < 1 || Lq > Lc) return PAFU_ERR_SHAPE;
   if (((long long)Lq / 32 + 1) * N > 0x7fffffffll) return PAFU_ERR_SHAPE;  // one-dimensional grid
   if (D != 64 && D != 128) return PAFU_ERR_SHAPE;
@@ -99,13 +102,13 @@ int check_attention(const void* Q, int Lq, const void* Kc, const void* Vc, int n
   if (ld_q < row || ld_n < row || ld_o < row || (n_kept > 0 && ld_c < row)) return PAFU_ERR_SHAPE;
   if (!Q || !Kn || !Vn || !O || (n_kept > 0 && (!Kc || !Vc))) return PAFU_ERR_NULL;
   if (!aligned16(Q) || !aligned16(Kn) || !aligned16(Vn) || !aligned16(O) || !aligned16(Kc) || !aligned16(Vc) ||
-      (ld_q * 2) % 16 != 0 || (ld_n * 2) % 16 != 0 || (ld_c * 2) % 16 != 0 || (ld_o * ob) % 16 != 0)
+      (ld_q * 2) % 16 != 0 || (ld_n * kvb) % 16 != 0 || (ld_c * kvb) % 16 != 0 || (ld_o * ob) % 16 != 0)
     return PAFU_ERR_ALIGN;
   const size_t o_bytes = (size_t)Lq * ld_o * ob;
-  if (overlaps(O, o_bytes, Q, (size_t)Lq * ld_q * 2) || overlaps(O, o_bytes, Kn, (size_t)Lc * ld_n * 2) ||
-      overlaps(O, o_bytes, Vn, (size_t)Lc * ld_n * 2) ||
-      (n_kept > 0 && (overlaps(O, o_bytes, Kc, (size_t)n_kept * ld_c * 2) ||
-                      overlaps(O, o_bytes, Vc, (size_t)n_kept * ld_c * 2))))
+  if (overlaps(O, o_bytes, Q, (size_t)Lq * ld_q * 2) || overlaps(O, o_bytes, Kn, (size_t)Lc * ld_n * kvb) ||
+      overlaps(O, o_bytes, Vn, (size_t)Lc * ld_n * kvb) ||
+      (n_kept > 0 && (overlaps(O, o_bytes, Kc, (size_t)n_kept * ld_c * kvb) ||
+                      overlaps(O, o_bytes, Vc, (size_t)n_kept * ld_c * kvb))))
     return PAFU_ERR_ALIAS;
   return PAFU_OK;
 }
@@ -130,6 +133,24 @@ bool spans_overlap(const Span& a, const Span& b) {
   return true;
 }
 
+// bf16 rows <-> 8-bit rows (both directions: `wide` is the bf16 side)
+int check_quant(const void* Kw, const void* Vw, long long ld_w, int rows, int N, int D, int ks, int vs, const void* Kq,
+                const void* Vq, long long ld_q, bool wide_is_output) {
+  if (rows < 0 || N <= 0 || D <= 0 || ((long long)N * D) % 8 != 0 || (long long)N * D > (1ll << 30)) return PAFU_ERR_SHAPE;
+  if (!scale_ok(ks) || !scale_ok(vs)) return PAFU_ERR_SHAPE;
+  const long long row = (long long)N * D;
+  if (ld_w < row || ld_q < row) return PAFU_ERR_SHAPE;
+  if (rows == 0) return PAFU_OK;
+  if (!Kw || !Vw || !Kq || !Vq) return PAFU_ERR_NULL;
+  if (!aligned16(Kw) || !aligned16(Vw) || !aligned16(Kq) || !aligned16(Vq) || (ld_w * 2) % 16 != 0 || ld_q % 16 != 0)
+    return PAFU_ERR_ALIGN;
+  const Span w0{Kw, rows, ld_w * 2, row * 2}, w1{Vw, rows, ld_w * 2, row * 2}, q0{Kq, rows, ld_q, row}, q1{Vq, rows, ld_q, row};
+  if (spans_overlap(w0, q0) || spans_overlap(w0, q1) || spans_overlap(w1, q0) || spans_overlap(w1, q1) ||
+      (wide_is_output ? spans_overlap(w0, w1) : spans_overlap(q0, q1)))
+    return PAFU_ERR_ALIAS;
+  return PAFU_OK;
+}
+
 // Everything a step reads and everything it writes (the workspace apart).  `scoring` is false for a layer that takes
 // its indices from another layer: then only the cache part counts.
 struct StepSpans {
@@ -139,8 +160,10 @@ struct StepSpans {
 void step_spans(const pafu_step_args* a, bool scoring, StepSpans& s) {
   const long long n = a->n, Lc = a->Lc, n_kept = a->k < a->n ? a->k : a->n;
   const bool single = a->mode == PAFU_MODE_SINGLE;
-  const long long rowb = (long long)a->N * a->D * 2;
-  const long long out_rows = n_kept + (single ? 0 : Lc);
+  const bool kv8 = a->kv_dtype == PAFU_FP8_E4M3;  // the quantised chunk rows then follow the retained ones in any mode
+  const long long kvb = kv8 ? 1 : 2;
+  const long long rowb = (long long)a->N * a->D * 2, rowkv = (long long)a->N * a->D * kvb;
+  const long long out_rows = n_kept + ((single && !kv8) ? 0 : Lc), sl_rows = n_kept + (single ? 0 : Lc);
   auto in = [&](const void* p, long long rows, long long ld, long long row) { s.in[s.n_in++] = Span{p, rows, ld, row}; };
   auto out = [&](const void* p, long long rows, long long ld, long long row) { s.out[s.n_out++] = Span{p, rows, ld, row}; };
   if (scoring) {
@@ -156,15 +179,15 @@ void step_spans(const pafu_step_args* a, bool scoring, StepSpans& s) {
     if (single) out(a->scores, 1, 0, (n + Lc) * 4);
     else in(a->SL_in, 1, 0, n * 4);
     out(a->ids, 1, 0, n_kept * 4);
-    out(a->SL_out, 1, 0, out_rows * 4);
+    out(a->SL_out, 1, 0, sl_rows * 4);
   }
-  in(a->K_cache, n, a->ld_cache * 2, rowb);
-  in(a->V_cache, n, a->ld_cache * 2, rowb);
+  in(a->K_cache, n, a->ld_cache * kvb, rowkv);
+  in(a->V_cache, n, a->ld_cache * kvb, rowkv);
   in(a->Q, Lc, a->ld_chunk * 2, rowb);
   in(a->K_chunk, Lc, a->ld_chunk * 2, rowb);
   in(a->V_chunk, Lc, a->ld_chunk * 2, rowb);
-  out(a->K_out, out_rows, a->ld_out * 2, rowb);
-  out(a->V_out, out_rows, a->ld_out * 2, rowb);
+  out(a->K_out, out_rows, a->ld_out * kvb, rowkv);
+  out(a->V_out, out_rows, a->ld_out * kvb, rowkv);
   out(a->O, Lc, a->ld_o * dtype_bytes(a->out_dtype), (long long)a->N * a->D * dtype_bytes(a->out_dtype));
 }
 // No output of a step may overlap one of its inputs, another output or the workspace (in ROLLOUT the output slab
@@ -225,11 +248,30 @@ size_t step_score_workspace(const pafu_step_args* a) {
   return a->n_out > 1 ? align_up(pafu_score_workspace_bytes(a->M)) : 0;
 }
 
+// The attention part of a layer's step.  bf16 K/V: retained rows in K_out/V_out, chunk rows read in place from
+// K_chunk/V_chunk.  8-bit K/V: the chunk is quantised behind the retained rows of K_out/V_out first (head dim 128
+// only) and attention reads both segments from there.
+int check_layer_attention(const pafu_step_args* a, int n_kept) {
+  if (a->kv_dtype != PAFU_FP8_E4M3)
+    return check_attention(a->Q, a->Lc, a->K_out, a->V_out, n_kept, a->K_chunk, a->V_chunk, a->Lc, a->N, a->D,
+                           a->ld_chunk, a->ld_out, a->ld_chunk, a->ld_o, a->block_len, a->O, a->out_dtype);
+  if (a->D != 128) return PAFU_ERR_SHAPE;
+  if (!a->K_out || !a->V_out) return PAFU_ERR_NULL;
+  char* kq = static_cast<char*>(a->K_out) + (long long)n_kept * a->ld_out;
+  char* vq = static_cast<char*>(a->V_out) + (long long)n_kept * a->ld_out;
+  int rc = check_quant(a->K_chunk, a->V_chunk, a->ld_chunk, a->Lc, a->N, a->D, a->k_scale_log2, a->v_scale_log2, kq, vq,
+                       a->ld_out, false);
+  if (rc) return rc;
+  return check_attention(a->Q, a->Lc, a->K_out, a->V_out, n_kept, kq, vq, a->Lc, a->N, a->D, a->ld_chunk, a->ld_out,
+                         a->ld_out, a->ld_o, a->block_len, a->O, a->out_dtype, 1);
+}
+
 // Validates a whole step without enqueuing anything.
 int check_step(const pafu_step_args* a) {
   if (!a) return PAFU_ERR_NULL;
   if (a->mode != PAFU_MODE_SINGLE && a->mode != PAFU_MODE_ROLLOUT) return PAFU_ERR_SHAPE;
   if (a->n < 0 || a->k < 0 || a->Lc < 1 || a->N < 1 || a->D < 1 || a->n_pinned < 0) return PAFU_ERR_SHAPE;
+  if (a->kv_dtype != PAFU_BF16 && a->kv_dtype != PAFU_FP8_E4M3) return PAFU_ERR_DTYPE;
   const int n_kept = a->k < a->n ? a->k : a->n;
   const bool single = a->mode == PAFU_MODE_SINGLE;
   if (a->workspace_bytes < step_score_workspace(a) || (a->workspace == nullptr && a->workspace_bytes > 0))
@@ -251,15 +293,15 @@ int check_step(const pafu_step_args* a) {
   rc = check_select(sel_scores, a->n, a->k, a->ids);
   if (rc) return rc;
   if (a->n > 0 && !a->SL_out) return PAFU_ERR_NULL;
-  rc = check_compact(a->K_cache, a->V_cache, sel_scores, a->ld_cache, a->n, a->ids, n_kept, a->N, a->D, PAFU_BF16,
+  rc = check_compact(a->K_cache, a->V_cache, sel_scores, a->ld_cache, a->n, a->ids, n_kept, a->N, a->D, a->kv_dtype,
                      a->K_out, a->V_out, a->SL_out, a->ld_out);
   if (rc) return rc;
-  rc = check_attention(a->Q, a->Lc, a->K_out, a->V_out, n_kept, a->K_chunk, a->V_chunk, a->Lc, a->N, a->D, a->ld_chunk,
-                       a->ld_out, a->ld_chunk, a->ld_o, a->block_len, a->O, a->out_dtype);
+  rc = check_layer_attention(a, n_kept);
   if (rc) return rc;
   if (!single) {
     if (!a->K_out || !a->V_out) return PAFU_ERR_NULL;
-    if (!aligned16(a->K_out) || !aligned16(a->V_out) || (a->ld_out * 2) % 16 != 0) return PAFU_ERR_ALIGN;
+    if (!aligned16(a->K_out) || !aligned16(a->V_out) || (a->ld_out * kv_dtype_bytes(a->kv_dtype)) % 16 != 0)
+      return PAFU_ERR_ALIGN;
     if (a->ld_out < (long long)a->N * a->D) return PAFU_ERR_SHAPE;
   }
   return check_step_alias(a, true);
@@ -318,23 +360,37 @@ int enqueue_kv(hipStream_t st, const pafu_step_args* a, const int* ids, const fl
                void* attn_ws, size_t attn_ws_bytes) {
   const int n_kept = a->k < a->n ? a->k : a->n;
   const float scale = a->softmax_scale > 0.f ? a->softmax_scale : 1.0f / sqrtf((float)a->D);
+  const bool kv8 = a->kv_dtype == PAFU_FP8_E4M3;
+  const int kvb = kv8 ? 1 : 2;
   int rc;
   if (a->n > 0) {
-    rc = launch_compact(st, a->K_cache, a->V_cache, sel_scores, a->ld_cache * 2, a->n, ids, n_kept, a->N * a->D * 2,
-                        a->K_out, a->V_out, SL_out, a->ld_out * 2);
+    rc = launch_compact(st, a->K_cache, a->V_cache, sel_scores, a->ld_cache * kvb, a->n, ids, n_kept, a->N * a->D * kvb,
+                        a->K_out, a->V_out, SL_out, a->ld_out * kvb);
+    if (rc) return rc;
+  }
+  char* ko = static_cast<char*>(a->K_out) + (long long)n_kept * a->ld_out * kvb;
+  char* vo = static_cast<char*>(a->V_out) + (long long)n_kept * a->ld_out * kvb;
+  if (kv8) {
+    // the chunk's K/V enter the cache as codes before attention: the chunk attends over exactly what later steps
+    // will find in the cache, and in a rollout nothing is left to append
+    rc = launch_quantize(st, a->K_chunk, a->V_chunk, a->ld_chunk * 2, a->Lc, a->N * a->D, a->k_scale_log2,
+                         a->v_scale_log2, ko, vo, a->ld_out);
     if (rc) return rc;
   }
   rc = record_stage(st, a, 3);
   if (rc) return rc;
-  rc = launch_attention(st, a->Q, a->Lc, a->K_out, a->V_out, n_kept, a->K_chunk, a->V_chunk, a->Lc, a->N, a->D,
-                        a->ld_chunk, a->ld_out, a->ld_chunk, a->ld_o, a->block_len, scale, a->O, a->out_dtype, attn_ws,
-                        attn_ws_bytes);
+  if (kv8)
+    rc = launch_attention(st, a->Q, a->Lc, a->K_out, a->V_out, n_kept, ko, vo, a->Lc, a->N, a->D, a->ld_chunk, a->ld_out,
+                          a->ld_out, a->ld_o, a->block_len, scale, a->O, a->out_dtype, attn_ws, attn_ws_bytes, nullptr, 0,
+                          PAFU_FP8_E4M3, ldexpf(1.0f, a->k_scale_log2), ldexpf(1.0f, a->v_scale_log2));
+  else
+    rc = launch_attention(st, a->Q, a->Lc, a->K_out, a->V_out, n_kept, a->K_chunk, a->V_chunk, a->Lc, a->N, a->D,
+                          a->ld_chunk, a->ld_out, a->ld_chunk, a->ld_o, a->block_len, scale, a->O, a->out_dtype, attn_ws,
+                          attn_ws_bytes);
   if (rc) return rc;
   rc = record_stage(st, a, 4);
   if (rc) return rc;
-  if (a->mode != PAFU_MODE_SINGLE) {
-    char* ko = static_cast<char*>(a->K_out) + (long long)n_kept * a->ld_out * 2;
-    char* vo = static_cast<char*>(a->V_out) + (long long)n_kept * a->ld_out * 2;
+  if (a->mode != PAFU_MODE_SINGLE && !kv8) {
     rc = launch_append(st, a->K_chunk, a->V_chunk, nullptr, a->ld_chunk * 2, a->Lc, a->N * a->D * 2, ko, vo, nullptr,
                        a->ld_out * 2);
     if (rc) return rc;
@@ -362,15 +418,16 @@ int check_layer_kv(const pafu_step_args* a, const pafu_step_args* idx) {
   if (a->mode != idx->mode || a->n != idx->n || a->k != idx->k || a->Lc != idx->Lc) return PAFU_ERR_SHAPE;
   if (a->N < 1 || a->D < 1) return PAFU_ERR_SHAPE;
   const int n_kept = a->k < a->n ? a->k : a->n;
-  int rc = check_compact(a->K_cache, a->V_cache, nullptr, a->ld_cache, a->n, idx->ids, n_kept, a->N, a->D, PAFU_BF16,
+  if (a->kv_dtype != PAFU_BF16 && a->kv_dtype != PAFU_FP8_E4M3) return PAFU_ERR_DTYPE;
+  int rc = check_compact(a->K_cache, a->V_cache, nullptr, a->ld_cache, a->n, idx->ids, n_kept, a->N, a->D, a->kv_dtype,
                          a->K_out, a->V_out, nullptr, a->ld_out);
   if (rc) return rc;
-  rc = check_attention(a->Q, a->Lc, a->K_out, a->V_out, n_kept, a->K_chunk, a->V_chunk, a->Lc, a->N, a->D, a->ld_chunk,
-                       a->ld_out, a->ld_chunk, a->ld_o, a->block_len, a->O, a->out_dtype);
+  rc = check_layer_attention(a, n_kept);
   if (rc) return rc;
   if (a->mode != PAFU_MODE_SINGLE) {
     if (!a->K_out || !a->V_out) return PAFU_ERR_NULL;
-    if (!aligned16(a->K_out) || !aligned16(a->V_out) || (a->ld_out * 2) % 16 != 0) return PAFU_ERR_ALIGN;
+    if (!aligned16(a->K_out) || !aligned16(a->V_out) || (a->ld_out * kv_dtype_bytes(a->kv_dtype)) % 16 != 0)
+      return PAFU_ERR_ALIGN;
     if (a->ld_out < (long long)a->N * a->D) return PAFU_ERR_SHAPE;
   }
   return check_step_alias(a, false);
@@ -455,9 +512,41 @@ int pafu_compact_kv(void* stream, const void* K, const void* V, const float* SL,
                     int count, int N, int D, int dtype, void* K_out, void* V_out, float* SL_out, long long ld_out) {
   int rc = check_compact(K, V, SL, ld_in, n, ids, count, N, D, dtype, K_out, V_out, SL_out, ld_out);
   if (rc) return rc;
-  const int eb = dtype_bytes(dtype);
+  const int eb = kv_dtype_bytes(dtype);
   return launch_compact(static_cast<hipStream_t>(stream), K, V, SL, ld_in * eb, n, ids, count, N * D * eb, K_out, V_out,
                         SL_out, ld_out * eb);
+}
+
+int pafu_quantize_kv(void* stream, const void* K, const void* V, long long ld_in, int rows, int N, int D,
+                     int k_scale_log2, int v_scale_log2, void* K_q, void* V_q, long long ld_out) {
+  int rc = check_quant(K, V, ld_in, rows, N, D, k_scale_log2, v_scale_log2, K_q, V_q, ld_out, false);
+  if (rc) return rc;
+  return launch_quantize(static_cast<hipStream_t>(stream), K, V, ld_in * 2, rows, N * D, k_scale_log2, v_scale_log2, K_q,
+                         V_q, ld_out);
+}
+
+int pafu_dequantize_kv(void* stream, const void* K_q, const void* V_q, long long ld_in, int rows, int N, int D,
+                       int k_scale_log2, int v_scale_log2, void* K, void* V, long long ld_out) {
+  int rc = check_quant(K, V, ld_out, rows, N, D, k_scale_log2, v_scale_log2, K_q, V_q, ld_in, true);
+  if (rc) return rc;
+  return launch_dequantize(static_cast<hipStream_t>(stream), K_q, V_q, ld_in, rows, N * D, k_scale_log2, v_scale_log2, K,
+                           V, ld_out * 2);
+}
+
+int pafu_chunk_attention_fp8(void* stream, const void* Q, int Lq, const void* Kc_q, const void* Vc_q, int n_kept,
+                             const void* Kn_q, const void* Vn_q, int Lc, int N, int D, long long ld_q, long long ld_c,
+                             long long ld_n, long long ld_o, int block_len, float softmax_scale, int k_scale_log2,
+                             int v_scale_log2, void* O, int out_dtype, void* workspace, size_t workspace_bytes) {
+  if (D != 128) return PAFU_ERR_SHAPE;  // the 8-bit tile path is built for head dim 128
+  if (!scale_ok(k_scale_log2) || !scale_ok(v_scale_log2)) return PAFU_ERR_SHAPE;
+  int rc = check_attention(Q, Lq, Kc_q, Vc_q, n_kept, Kn_q, Vn_q, Lc, N, D, ld_q, ld_c, ld_n, ld_o, block_len, O,
+                           out_dtype, 1);
+  if (rc) return rc;
+  if (workspace != nullptr && workspace_bytes > 0 && !aligned16(workspace)) return PAFU_ERR_ALIGN;
+  const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)D);
+  return launch_attention(static_cast<hipStream_t>(stream), Q, Lq, Kc_q, Vc_q, n_kept, Kn_q, Vn_q, Lc, N, D, ld_q, ld_c,
+                          ld_n, ld_o, block_len, scale, O, out_dtype, workspace, workspace_bytes, nullptr, 0,
+                          PAFU_FP8_E4M3, ldexpf(1.0f, k_scale_log2), ldexpf(1.0f, v_scale_log2));
 }
 
 size_t pafu_attention_workspace_bytes(int Lq, int N, int D) {

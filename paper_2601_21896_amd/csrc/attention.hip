@@ -62,6 +62,7 @@ struct AttnParams {
   long long ld_q, ld_c, ld_n, ld_o;
   int Lq, n_kept, Lc, block_len, N_heads;
   float scale_log2;  // softmax scale * log2(e)
+  float k_scale, v_scale;  // 8-bit K/V: the tensors' power-of-two scales (a stored code c stands for c * scale)
 };
 
 constexpr int kAtWaves = 8;
@@ -314,21 +315,39 @@ __device__ __forceinline__ long long uniform_i64(long long v) {
 // themselves (one 4-byte-per-lane load per wave and step, three steps ahead of the K tile that needs them, into a
 // small ring of their own), so the vector-memory queue stays one hand-counted stream and a lane picks up its row
 // index with one LDS read.
-template <int D, bool OUT_F32, bool GATHER>
+//
+// KV8: K and V (both key segments) are stored as 8-bit E4M3 codes with one power-of-two scale per tensor.  The tile
+// copies then move half the bytes, into a ring of raw tiles; every wave converts the 1 KB of each raw tile that it
+// copied itself to bf16 (scale applied, exact) and writes it, in the swizzled layout the fragment reads expect, into
+// one of two bf16 slots per tensor, one step before the matrix instructions read it.  The matrix instructions, the
+// softmax and the fragment reads are the bf16 kernel's; the arithmetic is no narrower than in the bf16 kernel.
+template <int D, bool OUT_F32, bool GATHER, bool KV8>
 __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnArgs args) {
+  static_assert(!KV8 || (D == 128 && !GATHER), "8-bit K/V: head dim 128, no index list");
   const AttnParams& p = args.p;
   const AttnWork& wk = args.w;
-  constexpr int ROWB = 2 * D;                  // bytes per K/V row of one head
-  constexpr int TILEB = kAtTileKeys * ROWB;    // bytes per K (or V) tile
-  constexpr int CH = D / 8;                    // 16-byte chunks per row
+  constexpr int ROWB = 2 * D;                  // bytes per bf16 K/V row of one head (what the fragment reads see)
+  constexpr int TILEB = kAtTileKeys * ROWB;    // bytes per bf16 K (or V) tile
+  constexpr int CH = D / 8;                    // 16-byte chunks per bf16 row
   constexpr int RPB = 256 / ROWB;              // rows per 256 bytes (one pass over all LDS banks)
-  constexpr int RPI = 1024 / ROWB;             // rows written by one wave-wide 16-byte-per-lane load
-  constexpr int LPT = TILEB / 1024 / kAtWaves; // such loads per wave per tensor per tile
+  constexpr int ELB = KV8 ? 1 : 2;             // bytes per stored K/V element
+  constexpr int SROWB = ELB * D;               // bytes per stored row of one head (what the tile copies move)
+  constexpr int STILEB = kAtTileKeys * SROWB;  // bytes per stored tile
+  constexpr int SCH = SROWB / 16;              // 16-byte chunks per stored row
+  constexpr int RPI = 1024 / SROWB;            // stored rows written by one wave-wide 16-byte-per-lane load
+  constexpr int LPT = STILEB / 1024 / kAtWaves;  // such loads per wave per tensor per tile
+  constexpr int CK = KV8 ? 2 : kAtStages;      // bf16 tile slots per tensor
+  constexpr int LEAD = KV8 ? kAtStages + 1 : kAtStages;  // a K tile is copied this many steps before the step that
+                                                         // computes the product of the tile BEFORE it (see the loop)
+  static_assert(LPT >= 1, "every wave copies part of every tile");
   constexpr int KD = D / 16;
   constexpr int DB = D / 32;
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds_raw[];
-  lds_byte* const k_ring = (lds_byte*)lds_raw;
-  lds_byte* const v_ring = k_ring + kAtStages * TILEB;
+  lds_byte* const k_ring = (lds_byte*)lds_raw;     // bf16 tiles the fragment reads address: CK slots
+  lds_byte* const v_ring = k_ring + CK * TILEB;
+  // 8-bit K/V: rings of raw tiles behind the bf16 slots (plain layout: lane l of wave w at w * 1024 + 16 l)
+  lds_byte* const k_land = KV8 ? v_ring + CK * TILEB : k_ring;   // where the tile copies land
+  lds_byte* const v_land = KV8 ? k_land + kAtStages * STILEB : v_ring;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // said to be uniform: what depends on it stays scalar
@@ -341,7 +360,7 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnArgs
   const int wg = xcd * (total / kAtXcds) + (xcd < total % kAtXcds ? xcd : total % kAtXcds) + xslot;
   const int L_B = p.block_len;
   const int n_total = p.n_kept + p.Lc;
-  const long long ldc_b = p.ld_c * 2, ldn_b = p.ld_n * 2;
+  const long long ldc_b = p.ld_c * ELB, ldn_b = p.ld_n * ELB;
 
   // ---- per-lane constants of the global -> LDS tile loads.  Load j of this wave fills LDS rows
   // (wave + W j) * RPI .. + RPI of a tile; lane -> (row, slot); the slot receives chunk (slot ^ swizzle(row)) of that
@@ -352,10 +371,10 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnArgs
   // of the swizzle period, so load j is load 0 with the scalar base moved on by j * kAtWaves * RPI rows)
   unsigned k_offc, k_offn, v_offc, v_offn;
   {
-    const int row = wave * RPI + lane / CH;
-    const int slot = lane % CH;
-    const int kch = slot ^ ((row / RPB) & (CH - 1));
-    const int vch = slot ^ (4 * ((row / RPB) & (CH / 4 - 1)));
+    const int row = wave * RPI + lane / SCH;
+    const int slot = lane % SCH;
+    const int kch = KV8 ? slot : slot ^ ((row / RPB) & (CH - 1));          // raw 8-bit tiles are not swizzled
+    const int vch = KV8 ? slot : slot ^ (4 * ((row / RPB) & (CH / 4 - 1)));
     k_offc = (unsigned)(row * ldc_b) + kch * 16;
     k_offn = (unsigned)(row * ldn_b) + kch * 16;
     v_offc = (unsigned)(row * ldc_b) + vch * 16;
@@ -374,7 +393,7 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnArgs
   const int cl = 2 * ((lane >> 4) & 1) + ((i16 & 3) >> 1);
   const int v_off = rr * ROWB + ((i16 & 1) << 3) + (cl << 4);
   const float sc = p.scale_log2;
-  int* const id_ring = reinterpret_cast<int*>(lds_raw + 2 * kAtStages * TILEB);
+  int* const id_ring = reinterpret_cast<int*>(lds_raw + 2 * kAtStages * TILEB);  // gather variant (bf16 K/V only)
 
   // ---- this workgroup's run of units [u, u_end) in the flattened (head, query tile, unit) list
   long long u, u_end;
@@ -454,8 +473,8 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnArgs
       const int tile = uniform_i32(tile_);
       const int stage = tile % kAtStages;
       const int key0 = tile * kAtTileKeys;
-      const char* base_c = reinterpret_cast<const char*>(cache + head_off);
-      const char* base_n = reinterpret_cast<const char*>(chunk + head_off) - (long long)p.n_kept * ldn_b;
+      const char* base_c = reinterpret_cast<const char*>(cache) + head_off * ELB;
+      const char* base_n = reinterpret_cast<const char*>(chunk) + head_off * ELB - (long long)p.n_kept * ldn_b;
       const bool all_cache = key0 + kAtTileKeys <= p.n_kept;
       const bool all_chunk = key0 >= p.n_kept && key0 + kAtTileKeys <= n_total;
       if (GATHER && all_cache) {  // workgroup-uniform
@@ -469,7 +488,7 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnArgs
 #pragma unroll
         for (int j = 0; j < LPT; ++j) {
           const int id = tile_id(tile, (wave + kAtWaves * j) * RPI + rl);
-          lds_byte* dst = ring + stage * TILEB + (wave + kAtWaves * j) * 1024;
+          lds_byte* dst = ring + stage * STILEB + (wave + kAtWaves * j) * 1024;
           dma_row_chunks_at(base_c, (unsigned)id * (unsigned)ldc_b + chunk16,
                             __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)dst));
         }
@@ -482,23 +501,23 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnArgs
         const unsigned off = from_cache ? offc : offn;
 #pragma unroll
         for (int j = 0; j < LPT; ++j) {
-          lds_byte* dst = ring + stage * TILEB + (wave + kAtWaves * j) * 1024;
+          lds_byte* dst = ring + stage * STILEB + (wave + kAtWaves * j) * 1024;
           dma_row_chunks_at(tile_base + (unsigned long long)(unsigned)(j * kAtWaves * RPI) * ld_b, off,
                             __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)dst));
         }
       } else {
 #pragma unroll
         for (int j = 0; j < LPT; ++j) {
-          const int row = (wave + kAtWaves * j) * RPI + lane / CH;
-          const int slot = lane % CH;
-          const int ch = is_v ? slot ^ (4 * ((row / RPB) & (CH / 4 - 1))) : slot ^ ((row / RPB) & (CH - 1));
+          const int row = (wave + kAtWaves * j) * RPI + lane / SCH;
+          const int slot = lane % SCH;
+          const int ch = KV8 ? slot : (is_v ? slot ^ (4 * ((row / RPB) & (CH / 4 - 1))) : slot ^ ((row / RPB) & (CH - 1)));
           int kidx = key0 + row;
           kidx = kidx < n_total ? kidx : n_total - 1;
           const bool in_cache = kidx < p.n_kept;
           if (GATHER && in_cache) kidx = tile_id(tile, row);
           const char* src = (in_cache ? base_c : base_n) +
                             (unsigned long long)(unsigned)kidx * (unsigned long long)(in_cache ? ldc_b : ldn_b) + ch * 16;
-          lds_byte* dst = ring + stage * TILEB + (wave + kAtWaves * j) * 1024;
+          lds_byte* dst = ring + stage * STILEB + (wave + kAtWaves * j) * 1024;
           dma_row_chunks(src, __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)dst));
         }
       }
@@ -508,11 +527,38 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnArgs
     // key axis hold clamped rows and are masked or never read.
     // In the gather variant the ids of tiles kt and kt-2 must already be visible in the ids ring.
     auto issue_tiles = [&](int kt) {  // kt relative to the segment
-      issue_one(tb + kt, p.Kc, p.Kn, k_ring, k_offc, k_offn, false);
-      if (kt >= 2) issue_one(tb + kt - 2, p.Vc, p.Vn, v_ring, v_offc, v_offn, true);
+      issue_one(tb + kt, p.Kc, p.Kn, k_land, k_offc, k_offn, false);
+      if (kt >= 2) issue_one(tb + kt - 2, p.Vc, p.Vn, v_land, v_offc, v_offn, true);
     };
-    auto k_addr = [&](int t) { return k_ring + ((tb + t) % kAtStages) * TILEB + k_off; };
-    auto v_addr = [&](int t) { return v_ring + ((tb + t) % kAtStages) * TILEB + v_off; };
+    auto k_addr = [&](int t) { return k_ring + ((tb + t) % CK) * TILEB + k_off; };
+    auto v_addr = [&](int t) { return v_ring + ((tb + t) % CK) * TILEB + v_off; };
+    // 8-bit K/V: this wave's 1 KB of raw tile t (the part it copied itself, so only its own copies must have landed)
+    // -> bf16, into the slot of tile t.  Lane l holds 16 codes of key row w * RPI + l / SCH, d = 16 (l % SCH) .. + 16:
+    // two 16-byte chunks of the bf16 row, stored with the swizzle of the fragment reads.
+    auto cook = [&](int t, bool is_v) {
+      typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
+      const int tile = tb + t;
+      const u32x4 raw = *(const lds_u32x4*)((is_v ? v_land : k_land) + (tile % kAtStages) * STILEB + wave * 1024 + lane * 16);
+      const int row = wave * RPI + lane / SCH, chunk = lane % SCH;
+      const int sw = is_v ? 4 * ((row / RPB) & (CH / 4 - 1)) : (row / RPB) & (CH - 1);
+      lds_byte* dst = (is_v ? v_ring : k_ring) + (tile % CK) * TILEB + row * ROWB;
+      const float scl = is_v ? p.v_scale : p.k_scale;
+      u32x4 lo, hi;
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        lo[2 * e] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[e], scl, false));
+        lo[2 * e + 1] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[e], scl, true));
+        hi[2 * e] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[2 + e], scl, false));
+        hi[2 * e + 1] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[2 + e], scl, true));
+      }
+      *(lds_u32x4*)(dst + (((2 * chunk) ^ sw) << 4)) = lo;
+      *(lds_u32x4*)(dst + (((2 * chunk + 1) ^ sw) << 4)) = hi;
+    };
+    // what a step does for the 8-bit tiles: K(t+2) and V(t) become bf16 one step before they are read
+    auto cook_step = [&](int t, int n_tiles_seg) {
+      if (t + 2 < n_tiles_seg) cook(t + 2, false);
+      if (t > 0) cook(t, true);
+    };
 
     // Q^T fragments (B operand): lane (query c, half g) holds Q[q][16 kk + 8 g .. +8]
     bf16x8 qf[KD];
@@ -533,6 +579,14 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnArgs
 #pragma unroll
     for (int i = 0; i < kAtStages; ++i) issue_tiles(i);
     wait_vmcnt<0>();
+    if (KV8) {  // the first product needs K(0), step 0 reads K(1) and (with P = 0) V(0)
+      cook(0, false);
+      cook(1, false);
+      cook(0, true);
+      __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the bf16 rows are written before the barrier lets others read
+      // the raw ring has kAtStages slots: K(kAtStages) goes where this wave's part of K(0) was, now that it is converted
+      issue_tiles(kAtStages);
+    }
     __builtin_amdgcn_s_barrier();
 
     // A wave whose 32 queries all lie past the end (the last query tile of a head is usually ragged) still loads its
@@ -542,7 +596,11 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnArgs
 #pragma unroll 1
       for (int t = 0; t < 2 * n_iter; ++t) {
         if (GATHER) issue_ids(tb + t + kAtStages + kAtIdLead);
-        if (!kAblateLoads) issue_tiles(t + kAtStages);
+        if (!kAblateLoads) issue_tiles(t + LEAD);
+        if (KV8) {
+          cook_step(t, 2 * n_iter);
+          __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
+        }
         wait_vmcnt<(kAtStages - 2) * (2 * LPT + (GATHER ? 1 : 0))>();
         __builtin_amdgcn_s_barrier();
       }
@@ -590,18 +648,22 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnArgs
         {
           const int t = 2 * T;
           if (GATHER) issue_ids(tb + t + kAtStages + kAtIdLead);
-          if (!kAblateLoads) issue_tiles(t + kAtStages);
+          if (!kAblateLoads) issue_tiles(t + LEAD);
+          if (KV8) cook_step(t, 2 * n_iter);
           if ((tb + t + 1) * kAtTileKeys > lim_min) attn_mask(s_a, (tb + t) * kAtTileKeys, lim, g);
           attn_step<D>(s_a, s_b, p_b, p_a, o, qf, msc, l_run, k_addr(t + 1), v_addr(t > 0 ? t - 1 : 0), kx2, vx2, sc);
+          if (KV8) __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): this step's bf16 rows are written
           wait_vmcnt<(kAtStages - 2) * (2 * LPT + (GATHER ? 1 : 0))>();
           __builtin_amdgcn_s_barrier();
         }
         {
           const int t = 2 * T + 1;
           if (GATHER) issue_ids(tb + t + kAtStages + kAtIdLead);
-          if (!kAblateLoads) issue_tiles(t + kAtStages);
+          if (!kAblateLoads) issue_tiles(t + LEAD);
+          if (KV8) cook_step(t, 2 * n_iter);
           if ((tb + t + 1) * kAtTileKeys > lim_min) attn_mask(s_b, (tb + t) * kAtTileKeys, lim, g);
           attn_step<D>(s_b, s_a, p_a, p_b, o, qf, msc, l_run, k_addr(T + 1 < n_iter ? t + 1 : t), v_addr(t - 1), kx2, vx2, sc);
+          if (KV8) __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
           wait_vmcnt<(kAtStages - 2) * (2 * LPT + (GATHER ? 1 : 0))>();
           __builtin_amdgcn_s_barrier();
         }
@@ -733,12 +795,12 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs args) {
   }
 }
 
-template <int D, bool OUT_F32, bool GATHER>
+template <int D, bool OUT_F32, bool GATHER, bool KV8 = false>
 int launch_variant(hipStream_t st, const AttnArgs& a) {
   static LdsLimit lds_limit;
-  const int rc = set_lds_limit(lds_limit, chunk_attention_kernel<D, OUT_F32, GATHER>, attn_lds_bytes(D, GATHER));
+  const int rc = set_lds_limit(lds_limit, chunk_attention_kernel<D, OUT_F32, GATHER, KV8>, attn_lds_bytes(D, GATHER));
   if (rc != PAFU_OK) return rc;
-  hipLaunchKernelGGL((chunk_attention_kernel<D, OUT_F32, GATHER>), dim3(a.w.n_wg), dim3(kAtThreads),
+  hipLaunchKernelGGL((chunk_attention_kernel<D, OUT_F32, GATHER, KV8>), dim3(a.w.n_wg), dim3(kAtThreads),
                      attn_lds_bytes(D, GATHER), st, a);
   if (a.w.split)
     hipLaunchKernelGGL((attn_combine_kernel<D, OUT_F32>), dim3(a.w.n_qt * a.p.N_heads * kAtCombineSplit), dim3(256), 0,
@@ -765,7 +827,8 @@ size_t attention_workspace_bytes(int D) {
 int launch_attention(hipStream_t st, const void* Q, int Lq, const void* Kc, const void* Vc, int n_kept,
                      const void* Kn, const void* Vn, int Lc, int N, int D, long long ld_q, long long ld_c,
                      long long ld_n, long long ld_o, int block_len, float scale, void* O, int out_dtype,
-                     void* workspace, size_t workspace_bytes, const int* ids, int n_cache) {
+                     void* workspace, size_t workspace_bytes, const int* ids, int n_cache, int kv_dtype,
+                     float k_scale, float v_scale) {
   AttnArgs a;
   AttnParams& p = a.p;
   p.ids = ids;
@@ -780,6 +843,8 @@ int launch_attention(hipStream_t st, const void* Q, int Lq, const void* Kc, cons
   p.Lq = Lq; p.n_kept = n_kept; p.Lc = Lc; p.N_heads = N;
   p.block_len = block_len < Lc ? block_len : Lc;  // blocks at least as long as the chunk mean "no mask"
   p.scale_log2 = scale * 1.44269504088896340736f;
+  p.k_scale = k_scale;
+  p.v_scale = v_scale;
 
   AttnWork& w = a.w;
   w.n_qt = (Lq + kAtBQ - 1) / kAtBQ;
@@ -816,6 +881,8 @@ int launch_attention(hipStream_t st, const void* Q, int Lq, const void* Kc, cons
     }
   }
   const bool f32 = out_dtype == PAFU_F32;
+  if (kv_dtype == PAFU_FP8_E4M3)  // validated by the caller: head dim 128, no index list
+    return f32 ? launch_variant<128, true, false, true>(st, a) : launch_variant<128, false, false, true>(st, a);
   return ids != nullptr && n_kept > 0 ? launch_dims<true>(st, a, D, f32) : launch_dims<false>(st, a, D, f32);
 }
 

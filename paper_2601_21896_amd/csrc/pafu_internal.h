@@ -73,7 +73,13 @@ int attention_study_build();  // 0 in the shipped library; the ablation mask of 
 int launch_attention(hipStream_t st, const void* Q, int Lq, const void* Kc, const void* Vc, int n_kept,
                      const void* Kn, const void* Vn, int Lc, int N, int D, long long ld_q, long long ld_c,
                      long long ld_n, long long ld_o, int block_len, float scale, void* O, int out_dtype,
-                     void* workspace, size_t workspace_bytes, const int* ids = nullptr, int n_cache = 0);
+                     void* workspace, size_t workspace_bytes, const int* ids = nullptr, int n_cache = 0,
+                     int kv_dtype = PAFU_BF16, float k_scale = 1.f, float v_scale = 1.f);
+// bf16 rows -> E4M3 codes (code = round(x / 2^scale_log2), saturating) and back; row_elems = N * D, strides in bytes.
+int launch_quantize(hipStream_t st, const void* K, const void* V, long long ld_in_bytes, int rows, int row_elems,
+                    int k_scale_log2, int v_scale_log2, void* Kq, void* Vq, long long ld_out_bytes);
+int launch_dequantize(hipStream_t st, const void* Kq, const void* Vq, long long ld_in_bytes, int rows, int row_elems,
+                      int k_scale_log2, int v_scale_log2, void* K, void* V, long long ld_out_bytes);
 // Compute units of the current GPU (cached per device; 256 if the query fails).
 int compute_units();
 
