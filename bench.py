@@ -424,14 +424,17 @@ def main():
         compact_ms = [se[0][2].elapsed_time(se[0][3]) for _, _, se in recorded]
         select_note = None
     else:
-        # Multi-layer steps: all scoring first, then ONE selection launch for up to 32 layers, then compaction and
-        # attention layer by layer.  A layer's compaction = end of the previous layer's attention to the start of its
-        # own; the selection launch = end of the last scoring to the start of layer 0's attention, less one compaction.
+        # Multi-layer steps: all scoring first, then ONE selection launch for up to 32 layers, then ONE compaction
+        # launch for up to 32 layers, then attention layer by layer.  The library records "after selection" once per
+        # step (on layer 0, or on the index layer); compaction = from there to the start of layer 0's attention,
+        # shared out over the layers.
         scoring = [idx_layer] if shared else list(range(n_layers))
+        sel_layer = idx_layer if shared else 0
         score_ms = [se[l][0].elapsed_time(se[l][1]) for _, _, se in recorded for l in scoring]
-        compact_ms = [se[l][4].elapsed_time(se[l + 1][3]) for _, _, se in recorded for l in range(n_layers - 1)]
-        select_ms = [max(0.0, se[scoring[-1]][1].elapsed_time(se[0][3]) - float(np.mean(compact_ms))) for _, _, se in recorded]
-        select_note = "one launch per step for %s" % ("the index layer" if shared else "all %d layers" % n_layers)
+        select_ms = [se[scoring[-1]][1].elapsed_time(se[sel_layer][2]) for _, _, se in recorded]
+        compact_ms = [se[sel_layer][2].elapsed_time(se[0][3]) / n_layers for _, _, se in recorded]
+        select_note = "one launch per step for %s; compaction: one launch for all %d layers, time per layer" % (
+            "the index layer" if shared else "all %d layers" % n_layers, n_layers)
     avg = {"score": float(np.mean(score_ms)), "select": float(np.mean(select_ms)), "compact": float(np.mean(compact_ms)),
            "attention": float(np.mean(attn_ms))}
     mn = {"score": float(np.min(score_ms)), "select": float(np.min(select_ms)), "compact": float(np.min(compact_ms)),

@@ -264,7 +264,8 @@ typedef struct pafu_step_args {
   /* Optional timing hooks (host handles, hipEvent_t passed as void*, each NULL = not recorded): recorded on the
    * step's stream before scoring [0], after scoring [1], after selection [2], after compaction [3] and after
    * attention [4] (ROLLOUT: the append follows [4]).  In the multi-layer steps, whose stages are reordered across
-   * layers, [0]/[1] bracket the layer's scoring and [3]/[4] its attention launch; [2] is not recorded there. */
+   * layers, [0]/[1] bracket a layer's scoring and [3]/[4] its attention launch; [2] is recorded once, after the
+   * selection launch, on args[0] (pafu_step_layers) or on the index layer (pafu_step_layers_shared). */
   void* stage_events[5];
   /* Storage of the K/V cache: PAFU_BF16 (0, the default) or PAFU_FP8_E4M3.  With the 8-bit format K_cache, V_cache,
    * K_out and V_out hold codes (ld_cache / ld_out count bytes; D must be 128), K_chunk / V_chunk / Q stay bf16, and
@@ -282,7 +283,8 @@ size_t pafu_step_workspace_bytes(const pafu_step_args* args /* host */);
 int pafu_step(void* stream, const pafu_step_args* args /* host */);
 /* The same step for n_layers independent layers (args[l] is layer l's arguments), enqueued on one stream.
  * The layers' stages are NOT enqueued layer by layer: every layer is scored first, then all selections run in one
- * launch (up to 32 score lists per launch), then compaction and attention follow layer by layer.  Every layer
+ * launch (up to 32 score lists per launch), then all compactions (one launch per 32 layers when the layers share
+ * n, k, N, D, the strides and the storage type; layer by layer otherwise), then attention layer by layer.  Every layer
  * therefore needs its own scores, ids, SL_out, K_out, V_out and O buffers, and no layer's output may overlap
  * another layer's input (PAFU_ERR_ALIAS); only the workspace may be shared between layers. */
 int pafu_step_layers(void* stream, const pafu_step_args* args /* host array */, int n_layers);

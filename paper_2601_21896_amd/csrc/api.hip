@@ -357,13 +357,13 @@ WsPart attention_ws(const pafu_step_args* a, bool scoring) {
 // The cache part of a step for one layer: compact K/V (and the score list when sel_scores is given) to `ids`,
 // attend over retained + chunk, and in ROLLOUT append the chunk's K/V behind the retained rows.
 int enqueue_kv(hipStream_t st, const pafu_step_args* a, const int* ids, const float* sel_scores, float* SL_out,
-               void* attn_ws, size_t attn_ws_bytes) {
+               void* attn_ws, size_t attn_ws_bytes, bool compacted = false) {
   const int n_kept = a->k < a->n ? a->k : a->n;
   const float scale = a->softmax_scale > 0.f ? a->softmax_scale : 1.0f / sqrtf((float)a->D);
   const bool kv8 = a->kv_dtype == PAFU_FP8_E4M3;
   const int kvb = kv8 ? 1 : 2;
   int rc;
-  if (a->n > 0) {
+  if (a->n > 0 && !compacted) {
     rc = launch_compact(st, a->K_cache, a->V_cache, sel_scores, a->ld_cache * kvb, a->n, ids, n_kept, a->N * a->D * kvb,
                         a->K_out, a->V_out, SL_out, a->ld_out * kvb);
     if (rc) return rc;
@@ -410,6 +410,41 @@ int enqueue_step(hipStream_t st, const pafu_step_args* a) {
   if (rc) return rc;
   const WsPart ws = attention_ws(a, true);
   return enqueue_kv(st, a, a->ids, sel_scores, a->SL_out, ws.p, ws.bytes);
+}
+
+// Multi-layer steps: when all layers share the cache geometry their compactions run as one launch per 32 layers
+// (each layer with its own tensors and index list; `shared_ids` non-null = one list for all).  Returns whether it did.
+bool enqueue_compact_batch(hipStream_t st, const pafu_step_args* args, int n_layers, const int* shared_ids,
+                           int score_layer /* -1: every layer compacts its own score list */, int* rc_out) {
+  *rc_out = PAFU_OK;
+  if (n_layers < 2) return false;
+  const pafu_step_args* a0 = &args[0];
+  const int kvb = kv_dtype_bytes(a0->kv_dtype);
+  const long long rowb = (long long)a0->N * a0->D * kvb;
+  if (a0->n <= 0 || rowb > (1 << 20) || !compact_batchable((int)rowb)) return false;
+  for (int l = 1; l < n_layers; ++l) {
+    const pafu_step_args* a = &args[l];
+    if (a->n != a0->n || a->k != a0->k || a->N != a0->N || a->D != a0->D || a->kv_dtype != a0->kv_dtype ||
+        a->ld_cache != a0->ld_cache || a->ld_out != a0->ld_out)
+      return false;
+  }
+  const int n_kept = a0->k < a0->n ? a0->k : a0->n;
+  CompactLayer layers[kCompactBatchMax];
+  for (int first = 0; first < n_layers; first += kCompactBatchMax) {
+    const int m = n_layers - first < kCompactBatchMax ? n_layers - first : kCompactBatchMax;
+    for (int i = 0; i < m; ++i) {
+      const pafu_step_args* a = &args[first + i];
+      const bool with_scores = score_layer < 0 || first + i == score_layer;
+      const float* sel = a->mode == PAFU_MODE_SINGLE ? a->scores : a->SL_in;
+      layers[i] = CompactLayer{static_cast<const char*>(a->K_cache), static_cast<const char*>(a->V_cache),
+                               static_cast<char*>(a->K_out), static_cast<char*>(a->V_out),
+                               shared_ids ? shared_ids : a->ids, with_scores ? sel : nullptr,
+                               with_scores ? a->SL_out : nullptr};
+    }
+    *rc_out = launch_compact_batch(st, layers, m, a0->ld_cache * kvb, a0->n, n_kept, (int)rowb, a0->ld_out * kvb);
+    if (*rc_out) return true;
+  }
+  return true;
 }
 
 // Validates the cache part of a layer that takes its indices from another layer.
@@ -661,10 +696,18 @@ int pafu_step_layers(void* stream, const pafu_step_args* args, int n_layers) {
       if (rc) return rc;
     }
   }
+  if (n_layers > 0) {  // the one "after selection" event of the step
+    int rc = record_stage(st, &args[0], 2);
+    if (rc) return rc;
+  }
+  int rc_batch;
+  const bool compacted = enqueue_compact_batch(st, args, n_layers, nullptr, -1, &rc_batch);
+  if (rc_batch) return rc_batch;
   for (int l = 0; l < n_layers; ++l) {
     const pafu_step_args* a = &args[l];
     const WsPart ws = attention_ws(a, true);
-    int rc = enqueue_kv(st, a, a->ids, a->mode == PAFU_MODE_SINGLE ? a->scores : a->SL_in, a->SL_out, ws.p, ws.bytes);
+    int rc = enqueue_kv(st, a, a->ids, a->mode == PAFU_MODE_SINGLE ? a->scores : a->SL_in, a->SL_out, ws.p, ws.bytes,
+                        compacted);
     if (rc) return rc;
   }
   return PAFU_OK;
@@ -693,13 +736,20 @@ int pafu_step_layers_shared(void* stream, const pafu_step_args* args, int n_laye
     rc = launch_select(st, sel_scores, idx->n, idx->k, idx->n_pinned, idx->ids, nullptr, nullptr);
     if (rc) return rc;
   }
+  rc = record_stage(st, idx, 2);
+  if (rc) return rc;
+  // every layer's cache is compacted to the one index list in one launch (per 32 layers) when the layers share the
+  // cache geometry, otherwise layer by layer
+  int rc_batch;
+  const bool compacted = enqueue_compact_batch(st, args, n_layers, idx->ids, index_layer, &rc_batch);
+  if (rc_batch) return rc_batch;
   for (int l = 0; l < n_layers; ++l) {
     const bool is_idx = l == index_layer;
     // a layer without a workspace of its own borrows the index layer's (the layers run one after the other)
     WsPart ws = attention_ws(&args[l], is_idx);
     if (ws.p == nullptr) ws = attention_ws(idx, true);
     rc = enqueue_kv(st, &args[l], idx->ids, is_idx ? sel_scores : nullptr, is_idx ? idx->SL_out : nullptr, ws.p,
-                    ws.bytes);
+                    ws.bytes, compacted);
     if (rc) return rc;
   }
   return PAFU_OK;

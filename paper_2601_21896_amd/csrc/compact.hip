@@ -52,6 +52,48 @@ __global__ __launch_bounds__(kCompactThreads) void compact_rows_kernel(
   }
 }
 
+// The same gather for several layers in one launch (multi-layer steps): a wave takes a retained row and moves it in
+// every layer of the batch, K and V, before it goes on to its next row.  The layers share the row geometry; each
+// brings its own tensors and index list (the same list for all of them when the indices are shared, Sec. 3.3).
+template <int CPL>
+__global__ __launch_bounds__(kCompactThreads) void compact_rows_batch_kernel(CompactBatch B, int n_layers,
+                                                                             long long ld_in, int n, int count,
+                                                                             int chunks, long long ld_out) {
+  const int lane = threadIdx.x & 63;
+  const int wave = blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+  const int n_waves = gridDim.x * kWavesPerBlock;
+  for (int r = wave; r < count; r += n_waves) {
+#pragma unroll 1
+    for (int l = 0; l < n_layers; ++l) {
+      const CompactLayer& L = B.layer[l];
+      const int id = L.ids[r];
+      if ((unsigned)id >= (unsigned)n) continue;  // invalid index: leave the row untouched
+      const u32x4* ks = reinterpret_cast<const u32x4*>(L.K + (long long)id * ld_in);
+      const u32x4* vs = reinterpret_cast<const u32x4*>(L.V + (long long)id * ld_in);
+      u32x4* kd = reinterpret_cast<u32x4*>(L.Ko + (long long)r * ld_out);
+      u32x4* vd = reinterpret_cast<u32x4*>(L.Vo + (long long)r * ld_out);
+      u32x4 kb[CPL], vb[CPL];
+#pragma unroll
+      for (int i = 0; i < CPL; ++i) {
+        const int c = lane + 64 * i;
+        if (c < chunks) {
+          kb[i] = __builtin_nontemporal_load(ks + c);
+          vb[i] = __builtin_nontemporal_load(vs + c);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < CPL; ++i) {
+        const int c = lane + 64 * i;
+        if (c < chunks) {
+          __builtin_nontemporal_store(kb[i], kd + c);
+          __builtin_nontemporal_store(vb[i], vd + c);
+        }
+      }
+      if (L.SL != nullptr && lane == 0) L.SLo[r] = L.SL[id];
+    }
+  }
+}
+
 // Rows longer than the unrolled path covers, or not a multiple of 16 bytes (then 4-byte words).
 template <typename W>
 __global__ __launch_bounds__(kCompactThreads) void compact_rows_generic_kernel(
@@ -139,6 +181,32 @@ int launch_compact(hipStream_t st, const void* K, const void* V, const float* SL
                        count, row_bytes / 4, ko, vo, SL_out, ld_out_bytes);
   }
   return check_launch();
+}
+
+bool compact_batchable(int row_bytes) { return row_bytes % 16 == 0 && row_bytes <= 4 * 1024; }
+
+int launch_compact_batch(hipStream_t st, const CompactLayer* layers, int n_layers, long long ld_in_bytes, int n,
+                         int count, int row_bytes, long long ld_out_bytes) {
+  if (count <= 0 || n_layers <= 0) return PAFU_OK;
+  const int chunks = row_bytes / 16;
+  const int cpl = (chunks + 63) / 64;
+  for (int first = 0; first < n_layers; first += kCompactBatchMax) {
+    const int m = n_layers - first < kCompactBatchMax ? n_layers - first : kCompactBatchMax;
+    CompactBatch B;
+    for (int i = 0; i < kCompactBatchMax; ++i) B.layer[i] = layers[first + (i < m ? i : 0)];
+    const dim3 grid(grid_for_rows(count)), block(kCompactThreads);
+#define PAFU_COMPACT_BATCH_CASE(C)                                                                                \
+  hipLaunchKernelGGL(compact_rows_batch_kernel<C>, grid, block, 0, st, B, m, ld_in_bytes, n, count, chunks,      \
+                     ld_out_bytes)
+    if (cpl <= 1) PAFU_COMPACT_BATCH_CASE(1);
+    else if (cpl <= 2) PAFU_COMPACT_BATCH_CASE(2);
+    else if (cpl <= 3) PAFU_COMPACT_BATCH_CASE(3);
+    else PAFU_COMPACT_BATCH_CASE(4);
+#undef PAFU_COMPACT_BATCH_CASE
+    const int rc = check_launch();
+    if (rc) return rc;
+  }
+  return PAFU_OK;
 }
 
 int launch_append(hipStream_t st, const void* K, const void* V, const float* S, long long ld_in_bytes, int rows,

@@ -41,6 +41,25 @@ inline bool overlaps(const void* a, size_t a_bytes, const void* b, size_t b_byte
 int launch_compact(hipStream_t st, const void* K, const void* V, const float* SL, long long ld_in_bytes, int n,
                    const int* ids, int count, int row_bytes, void* K_out, void* V_out, float* SL_out,
                    long long ld_out_bytes);
+// One layer of a batched compaction: its cache tensors, output slabs, index list and (optionally) score list.
+struct CompactLayer {
+  const char* K;
+  const char* V;
+  char* Ko;
+  char* Vo;
+  const int* ids;
+  const float* SL;  // null: no score list for this layer
+  float* SLo;
+};
+constexpr int kCompactBatchMax = 32;  // layers per launch (they travel as kernel arguments)
+struct CompactBatch {
+  CompactLayer layer[kCompactBatchMax];
+};
+// Rows up to 4 KiB and a multiple of 16 bytes can go through the batched kernel.
+bool compact_batchable(int row_bytes);
+// The layers share n, count, the row size and both strides.
+int launch_compact_batch(hipStream_t st, const CompactLayer* layers, int n_layers, long long ld_in_bytes, int n,
+                         int count, int row_bytes, long long ld_out_bytes);
 int launch_append(hipStream_t st, const void* K, const void* V, const float* S, long long ld_in_bytes, int rows,
                   int row_bytes, void* K_out, void* V_out, float* S_out, long long ld_out_bytes);
 // One top-k selection: scores [n] -> the min(k, n) retained indices, ascending (out_count may be null).
