@@ -137,6 +137,14 @@ int pafu_compact_kv(void* stream, const void* K, const void* V, const float* SL,
                     const int* ids, int count, int N, int D, int dtype, void* K_out, void* V_out,
                     float* SL_out, long long ld_out);
 
+/* pafu_compact_kv_counted - the same with the row count read on the device: `count` is a device int32 (what
+ * pafu_select_topk writes to out_count), so selection and compaction can be enqueued without a host round trip when
+ * the count is not known on the host.  At most max_count rows are moved (the capacity of ids and of the outputs, and
+ * what the launch is sized for); a negative device count moves nothing.  max_count <= n. */
+int pafu_compact_kv_counted(void* stream, const void* K, const void* V, const float* SL, long long ld_in, int n,
+                            const int* ids, const int* count /* device */, int max_count, int N, int D, int dtype,
+                            void* K_out, void* V_out, float* SL_out, long long ld_out);
+
 /* ------------------------------------------------------------------------------------------
  * pafu_chunk_attention - attention of the chunk's queries over retained cache + chunk.
  * Sec. 3.2 (P = softmax(Q K^T / sqrt(D)), block boundaries from L_B); App. A (L_B = chunk length).

@@ -23,7 +23,7 @@ SYMBOLS = (
     "pafu_strerror", "pafu_last_hip_error", "pafu_version", "pafu_study_build", "pafu_launch_probe",
     "pafu_score_workspace_bytes", "pafu_score", "pafu_score_static",
     "pafu_select_workspace_bytes", "pafu_select_topk", "pafu_select_topk_pinned",
-    "pafu_compact_kv",
+    "pafu_compact_kv", "pafu_compact_kv_counted",
     "pafu_attention_workspace_bytes", "pafu_chunk_attention", "pafu_chunk_attention_gather",
     "pafu_quantize_kv", "pafu_dequantize_kv", "pafu_chunk_attention_fp8",
     "pafu_sse_workspace_bytes", "pafu_sse_score",
@@ -96,6 +96,10 @@ def _lib():
         lib.pafu_compact_kv.restype = c_int
         lib.pafu_compact_kv.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_longlong, c_int, c_void_p, c_int,
                                         c_int, c_int, c_int, c_void_p, c_void_p, c_void_p, c_longlong]
+        lib.pafu_compact_kv_counted.restype = c_int
+        lib.pafu_compact_kv_counted.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_longlong, c_int, c_void_p,
+                                                c_void_p, c_int, c_int, c_int, c_int, c_void_p, c_void_p, c_void_p,
+                                                c_longlong]
         lib.pafu_attention_workspace_bytes.restype = c_size_t
         lib.pafu_attention_workspace_bytes.argtypes = [c_int, c_int, c_int]
         lib.pafu_chunk_attention.restype = c_int
@@ -268,6 +272,17 @@ def pafu_compact_kv(K, V, SL, ids, count, K_out, V_out, SL_out, stream=None, n=N
     rc = _lib().pafu_compact_kv(_stream(stream), _ptr(K), _ptr(V), _ptr(SL), K.stride(0), n, _ptr(ids), count, N, D,
                                 _dtype_code(K), _ptr(K_out), _ptr(V_out), _ptr(SL_out), K_out.stride(0))
     _check(rc, "pafu_compact_kv")
+    return K_out, V_out, SL_out
+
+
+def pafu_compact_kv_counted(K, V, SL, ids, count_dev, max_count, K_out, V_out, SL_out, stream=None, n=None):
+    """pafu_compact_kv with the row count in a device int32 tensor (as written by pafu_select_topk)."""
+    n = K.shape[0] if n is None else n
+    N, D = K.shape[1], K.shape[2]
+    rc = _lib().pafu_compact_kv_counted(_stream(stream), _ptr(K), _ptr(V), _ptr(SL), K.stride(0), n, _ptr(ids),
+                                        _ptr(count_dev), max_count, N, D, _dtype_code(K), _ptr(K_out), _ptr(V_out),
+                                        _ptr(SL_out), K_out.stride(0))
+    _check(rc, "pafu_compact_kv_counted")
     return K_out, V_out, SL_out
 
 

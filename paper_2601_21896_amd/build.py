@@ -16,6 +16,9 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
+    # the attention step is one fully unrolled 32-slot block; above the default threshold the unroller keeps a partial
+    # loop, the register arrays get indexed dynamically and spill
+    "-mllvm", "-pragma-unroll-threshold=200000",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]
 

@@ -584,6 +584,17 @@ int pafu_chunk_attention_fp8(void* stream, const void* Q, int Lq, const void* Kc
                           PAFU_FP8_E4M3, ldexpf(1.0f, k_scale_log2), ldexpf(1.0f, v_scale_log2));
 }
 
+int pafu_compact_kv_counted(void* stream, const void* K, const void* V, const float* SL, long long ld_in, int n,
+                            const int* ids, const int* count, int max_count, int N, int D, int dtype, void* K_out,
+                            void* V_out, float* SL_out, long long ld_out) {
+  if (max_count > 0 && count == nullptr) return PAFU_ERR_NULL;
+  int rc = check_compact(K, V, SL, ld_in, n, ids, max_count, N, D, dtype, K_out, V_out, SL_out, ld_out);
+  if (rc) return rc;
+  const int eb = kv_dtype_bytes(dtype);
+  return launch_compact(static_cast<hipStream_t>(stream), K, V, SL, ld_in * eb, n, ids, max_count, N * D * eb, K_out,
+                        V_out, SL_out, ld_out * eb, count);
+}
+
 size_t pafu_attention_workspace_bytes(int Lq, int N, int D) {
   (void)Lq; (void)N;
   return (D == 64 || D == 128) ? attention_workspace_bytes(D) : 0;

@@ -159,7 +159,7 @@ __device__ __forceinline__ void attn_step(const f32x16 (&s_cur)[2], f32x16 (&s_n
   constexpr int NSLOT = NS + NP;   // MFMAs per step (NS == NP for D = 64 and 128)
   constexpr int A_SLOTS = 5;       // slots that carry the max / threshold work
   static_assert(NS == NP, "the slot pattern alternates one MFMA of each product");
-  float alpha, mx, msc_new, psum = 0.f;
+  float alpha, mx, msc_new, psum = 0.f, q0 = 0.f, q1 = 0.f;
   bool grow;
 
   // slot i = 2 m + w: w = 0 -> S^T MFMA number m, w = 1 -> O^T MFMA number m.
@@ -235,15 +235,28 @@ __device__ __forceinline__ void attn_step(const f32x16 (&s_cur)[2], f32x16 (&s_n
           asm volatile("" : "+v"(a0), "+v"(a1));  // the slice may not rise above the previous MFMA ...
           const float pe0 = __builtin_amdgcn_exp2f(fmaf(a0, sc, -msc_new));
           const float pe1 = __builtin_amdgcn_exp2f(fmaf(a1, sc, -msc_new));
-          psum += pe0;
-          psum += pe1;
-          unsigned pk = pack_bf16(pe0, pe1);
-          asm volatile("" : "+v"(pk), "+v"(psum));  // ... nor sink below the next one
-          p_cur[2 * kb + (r >> 3)][(r & 7) >> 1] = pk;
+          // the sums and the pack of the PREVIOUS unit go here, behind this unit's exponentials: a transcendental
+          // result takes several issue slots to arrive, and adding it right away stalls the wave
+          if (u > 0) {
+            const int kbp = (u - 1) >> 3, rp = 2 * ((u - 1) & 7);
+            psum += q0;
+            psum += q1;
+            unsigned pk = pack_bf16(q0, q1);
+            asm volatile("" : "+v"(pk), "+v"(psum));
+            p_cur[2 * kbp + (rp >> 3)][(rp & 7) >> 1] = pk;
+          }
+          q0 = pe0;
+          q1 = pe1;
+          asm volatile("" : "+v"(q0), "+v"(q1));  // ... nor sink below the next one
         }
       }
     }
     __builtin_amdgcn_sched_barrier(0);
+  }
+  if (!kAblateSoftmax) {  // the last unit
+    psum += q0;
+    psum += q1;
+    p_cur[3][3] = pack_bf16(q0, q1);
   }
   l_run = fmaf(l_run, alpha, psum);
   // O^T now holds tiles < t scaled by the old maximum; bring it to the new one before tile t is added

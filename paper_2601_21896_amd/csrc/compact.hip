@@ -20,10 +20,14 @@ template <int CPL>  // 16-byte chunks per lane per row (row_bytes <= CPL*1024)
 __global__ __launch_bounds__(kCompactThreads) void compact_rows_kernel(
     const char* __restrict__ K, const char* __restrict__ V, const float* __restrict__ SL, long long ld_in, int n,
     const int* __restrict__ ids, int count, int chunks, char* __restrict__ Ko, char* __restrict__ Vo,
-    float* __restrict__ SLo, long long ld_out) {
+    float* __restrict__ SLo, long long ld_out, const int* __restrict__ count_dev) {
   const int lane = threadIdx.x & 63;
   const int wave = blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
   const int n_waves = gridDim.x * kWavesPerBlock;
+  if (count_dev != nullptr) {  // the row count lives on the device (written by the selection): at most `count` rows
+    const int c = *count_dev;
+    count = c < count ? (c < 0 ? 0 : c) : count;
+  }
   for (int r = wave; r < count; r += n_waves) {
     const int id = ids[r];
     if ((unsigned)id >= (unsigned)n) continue;  // invalid index: leave the row untouched
@@ -99,10 +103,14 @@ template <typename W>
 __global__ __launch_bounds__(kCompactThreads) void compact_rows_generic_kernel(
     const char* __restrict__ K, const char* __restrict__ V, const float* __restrict__ SL, long long ld_in, int n,
     const int* __restrict__ ids, int count, int words, char* __restrict__ Ko, char* __restrict__ Vo,
-    float* __restrict__ SLo, long long ld_out) {
+    float* __restrict__ SLo, long long ld_out, const int* __restrict__ count_dev) {
   const int lane = threadIdx.x & 63;
   const int wave = blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
   const int n_waves = gridDim.x * kWavesPerBlock;
+  if (count_dev != nullptr) {
+    const int c = *count_dev;
+    count = c < count ? (c < 0 ? 0 : c) : count;
+  }
   for (int r = wave; r < count; r += n_waves) {
     const int id = ids[r];
     if ((unsigned)id >= (unsigned)n) continue;
@@ -151,7 +159,7 @@ int grid_for_rows(int rows) {
 
 int launch_compact(hipStream_t st, const void* K, const void* V, const float* SL, long long ld_in_bytes, int n,
                    const int* ids, int count, int row_bytes, void* K_out, void* V_out, float* SL_out,
-                   long long ld_out_bytes) {
+                   long long ld_out_bytes, const int* count_dev) {
   if (count <= 0) return PAFU_OK;
   const dim3 grid(grid_for_rows(count)), block(kCompactThreads);
   const char* k = static_cast<const char*>(K);
@@ -163,7 +171,7 @@ int launch_compact(hipStream_t st, const void* K, const void* V, const float* SL
     const int cpl = (chunks + 63) / 64;
 #define PAFU_COMPACT_CASE(C)                                                                                  \
   hipLaunchKernelGGL(compact_rows_kernel<C>, grid, block, 0, st, k, v, SL, ld_in_bytes, n, ids, count, chunks, \
-                     ko, vo, SL_out, ld_out_bytes)
+                     ko, vo, SL_out, ld_out_bytes, count_dev)
     if (cpl <= 1) PAFU_COMPACT_CASE(1);
     else if (cpl <= 2) PAFU_COMPACT_CASE(2);
     else if (cpl <= 3) PAFU_COMPACT_CASE(3);
@@ -175,10 +183,10 @@ int launch_compact(hipStream_t st, const void* K, const void* V, const float* SL
 #undef PAFU_COMPACT_CASE
   } else if (row_bytes % 16 == 0) {
     hipLaunchKernelGGL(compact_rows_generic_kernel<u32x4>, grid, block, 0, st, k, v, SL, ld_in_bytes, n, ids, count,
-                       row_bytes / 16, ko, vo, SL_out, ld_out_bytes);
+                       row_bytes / 16, ko, vo, SL_out, ld_out_bytes, count_dev);
   } else {
     hipLaunchKernelGGL(compact_rows_generic_kernel<unsigned int>, grid, block, 0, st, k, v, SL, ld_in_bytes, n, ids,
-                       count, row_bytes / 4, ko, vo, SL_out, ld_out_bytes);
+                       count, row_bytes / 4, ko, vo, SL_out, ld_out_bytes, count_dev);
   }
   return check_launch();
 }

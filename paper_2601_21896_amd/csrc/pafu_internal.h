@@ -40,7 +40,7 @@ inline bool overlaps(const void* a, size_t a_bytes, const void* b, size_t b_byte
 // Stage launchers (validated arguments only).
 int launch_compact(hipStream_t st, const void* K, const void* V, const float* SL, long long ld_in_bytes, int n,
                    const int* ids, int count, int row_bytes, void* K_out, void* V_out, float* SL_out,
-                   long long ld_out_bytes);
+                   long long ld_out_bytes, const int* count_dev = nullptr);
 // One layer of a batched compaction: its cache tensors, output slabs, index list and (optionally) score list.
 struct CompactLayer {
   const char* K;

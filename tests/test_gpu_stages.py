@@ -65,6 +65,39 @@ def test_compact_skips_invalid_ids_and_optional_scores():
             assert torch.equal(Ko[r], K[i]) and torch.equal(Vo[r], V[i])
 
 
+def test_compact_with_the_count_on_the_device():
+    # selection writes the count, compaction reads it there: no host round trip in between
+    n, N, D, k = 3000, 4, 128, 1111
+    g = torch.Generator(device=DEV)
+    g.manual_seed(3)
+    K = torch.randn(n, N, D, device=DEV, generator=g).to(torch.bfloat16)
+    V = torch.randn(n, N, D, device=DEV, generator=g).to(torch.bfloat16)
+    SL = torch.randn(n, device=DEV, generator=g)
+    cap = 1500                                              # room for more rows than the budget keeps
+    ids = torch.full((cap,), -1, dtype=torch.int32, device=DEV)
+    cnt = torch.zeros(1, dtype=torch.int32, device=DEV)
+    Ko = torch.full((cap, N, D), 7.0, device=DEV, dtype=torch.bfloat16)
+    Vo = torch.full((cap, N, D), 7.0, device=DEV, dtype=torch.bfloat16)
+    SLo = torch.full((cap,), 7.0, device=DEV)
+    B.pafu_select_topk(SL, k, ids, cnt)
+    B.pafu_compact_kv_counted(K, V, SL, ids, cnt, cap, Ko, Vo, SLo)
+    torch.cuda.synchronize()
+    want_ids = orc.select_topk(host(SL), k)
+    Kw, Vw, SLw = orc.compact_kv(bits(K), bits(V), bits(SL), want_ids)
+    assert int(cnt.item()) == k
+    assert np.array_equal(bits(Ko[:k]), Kw) and np.array_equal(bits(Vo[:k]), Vw) and np.array_equal(bits(SLo[:k]), SLw)
+    assert torch.all(Ko[k:] == 7.0) and torch.all(Vo[k:] == 7.0) and torch.all(SLo[k:] == 7.0)   # nothing past the count
+    # a device count above the capacity is clamped to it, a negative one moves nothing
+    cnt.fill_(10 ** 6)
+    ids2 = torch.arange(cap, dtype=torch.int32, device=DEV)
+    B.pafu_compact_kv_counted(K, V, SL, ids2, cnt, cap, Ko, Vo, SLo)
+    cnt.fill_(-5)
+    Ko2 = torch.full((cap, N, D), 3.0, device=DEV, dtype=torch.bfloat16)
+    B.pafu_compact_kv_counted(K, V, None, ids2, cnt, cap, Ko2, Vo, None)
+    torch.cuda.synchronize()
+    assert torch.equal(Ko, K[:cap]) and torch.all(Ko2 == 3.0)
+
+
 # ------------------------------------------------------------------------------- select
 def _run_select(s_np, k):
     n = len(s_np)
