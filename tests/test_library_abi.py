@@ -32,7 +32,14 @@ def test_every_declared_symbol_is_exported():
 def test_workspace_queries():
     assert binding.pafu_score_workspace_bytes(256) >= 257 * 4
     assert binding.pafu_select_workspace_bytes(32760) >= 0
-    assert binding.pafu_attention_workspace_bytes(4680, 12, 128) >= 0
+    # two partial-result slots (256 queries x (D + 2) floats) for each of at most 256 runs
+    assert binding.pafu_attention_workspace_bytes(4680, 12, 128) == 2 * 256 * 256 * (128 + 2) * 4
+    assert binding.pafu_attention_workspace_bytes(64, 2, 64) == 2 * 256 * 256 * (64 + 2) * 4
+    assert binding.pafu_attention_workspace_bytes(64, 2, 96) == 0
+    a = _fake_step(A)
+    assert binding.pafu_step_workspace_bytes(a) == 0 + binding.pafu_attention_workspace_bytes(20, 2, 64)
+    a.n_out = 5
+    assert binding.pafu_step_workspace_bytes(a) == 256 + binding.pafu_attention_workspace_bytes(20, 2, 64)
 
 
 A = 0x10000   # a fake, 16-byte aligned "device address": validation must fail before it is ever used
@@ -188,6 +195,54 @@ def test_step_rejects_aliased_buffers():
     pair = (binding.pafu_step_args * 2)(_fake_step(A), _fake_step(A + 0x8000000))
     pair[0].O = pair[1].O
     assert lib.pafu_step_layers_shared(None, pair, 2, 1) == -6
+
+
+def test_new_entry_points_reject_bad_arguments():
+    lib = binding.library()
+    # pafu_score_static: same checks as pafu_score, plus the limit of its static scratch
+    f = lib.pafu_score_static
+
+    def call(x0=A, T=10, Fs=128, ld=128, dt=0, W1=A + 0x100000, W2=A + 0x200000, M=32, no=3, act=0, out=A + 0x300000):
+        return f(None, x0, None, None, 1, T, Fs, ld, dt, W1, None, W2, None, M, no, act, out)
+    assert call(x0=None) == -1
+    assert call(M=0) == -2
+    assert call(dt=2) == -3                        # the 8-bit format is for K/V tensors only
+    assert call(ld=132) == -4
+    assert call(M=8193) == -5                      # beyond the static scratch
+    # pafu_compact_kv_counted
+    g = lib.pafu_compact_kv_counted
+    ok = dict(K=A, V=A + 0x100000, SL=None, ld=1536, n=100, ids=A + 0x200000, cnt=A + 0x600000, mx=50, N=12, D=128, dt=0,
+              Ko=A + 0x300000, Vo=A + 0x400000, SLo=None, ldo=1536)
+
+    def ccall(**kw):
+        a = dict(ok); a.update(kw)
+        return g(None, a["K"], a["V"], a["SL"], a["ld"], a["n"], a["ids"], a["cnt"], a["mx"], a["N"], a["D"], a["dt"],
+                 a["Ko"], a["Vo"], a["SLo"], a["ldo"])
+    assert ccall(cnt=None) == -1
+    assert ccall(mx=101) == -2
+    assert ccall(Ko=A) == -6
+    assert ccall(dt=9) == -3
+    assert ccall(mx=0, cnt=None, K=None) == 0
+    # pafu_quantize_kv / pafu_dequantize_kv
+    q = lib.pafu_quantize_kv
+    assert q(None, None, A, 256, 10, 2, 128, 0, 0, A + 0x200000, A + 0x300000, 256) == -1
+    assert q(None, A, A + 0x100000, 256, 10, 2, 127, 0, 0, A + 0x200000, A + 0x300000, 256) == -2     # N * D not a multiple of 8
+    assert q(None, A, A + 0x100000, 256, 10, 2, 128, 65, 0, A + 0x200000, A + 0x300000, 256) == -2    # scale exponent
+    assert q(None, A, A + 0x100000, 256, 10, 2, 128, 0, 0, A + 0x200000, A + 0x300000, 264) == -4     # byte stride % 16
+    assert q(None, A, A + 0x100000, 256, 0, 2, 128, 0, 0, None, None, 256) == 0
+    assert lib.pafu_dequantize_kv(None, A, A + 0x100000, 256, 10, 2, 128, 0, 0, A + 0x200000, A + 0x200100, 256) == -6
+    # a step with the 8-bit cache: head dim 128 only, and the output slab counts with the chunk rows
+    a = _fake_step(A, N=2, D=64)
+    a.kv_dtype = 2
+    assert lib.pafu_step(None, ctypes.byref(a)) == -2
+    a = _fake_step(A, N=1, D=128)
+    a.kv_dtype = 7
+    assert lib.pafu_step(None, ctypes.byref(a)) == -3
+    a = _fake_step(A, N=1, D=128)
+    a.kv_dtype = 2
+    a.Q = a.K_out + 50 * 128 + 16 * 128                  # inside the rows where the quantised chunk goes (SINGLE mode too)
+    assert lib.pafu_step(None, ctypes.byref(a)) == -6
+    assert lib.pafu_study_build() == 0
 
 
 def test_sse_rejects_bad_arguments_and_reports_its_workspace():
