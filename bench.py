@@ -241,7 +241,9 @@ def rollout(a, torch, np, B, wl):
     flops = 4.0 * Lc * (n_kept + Lc) * D * N
     attn_ms = float(np.mean(st[:, 3]))
     peak_cache = 2 * (cap * N * D * kvb * 2 + cap * 4)
-    bytes_compact = 2 * (2 * n_kept * N * D * kvb) + 3 * n_kept * 4
+    # between the events around compaction: the gather of the retained rows (read + write, K and V, ids, scores) and
+    # the chunk's rows put behind them (bf16: copied by the same launch; 8-bit: quantised, 2 bytes in, 1 out)
+    bytes_compact = 2 * (2 * n_kept * N * D * kvb) + 3 * n_kept * 4 + 2 * Lc * N * D * (2 + kvb)
     out = {
         "metric": METRIC, "value": float(np.median(steady)), "unit": "ms",
         "n_gpus": 1, "steps": len(steady), "warmup": n_chunks + 5, "ms_per_step": float(np.median(steady)),

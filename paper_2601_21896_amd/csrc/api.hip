@@ -363,9 +363,15 @@ int enqueue_kv(hipStream_t st, const pafu_step_args* a, const int* ids, const fl
   const bool kv8 = a->kv_dtype == PAFU_FP8_E4M3;
   const int kvb = kv8 ? 1 : 2;
   int rc;
+  // In a rollout with bf16 storage the compaction launch also moves the chunk's rows behind the retained ones: the
+  // append costs no launch of its own, and attention (which reads the chunk from its own buffers) does not wait for it.
+  bool appended = false;
   if (a->n > 0 && !compacted) {
+    CompactTail tail{static_cast<const char*>(a->K_chunk), static_cast<const char*>(a->V_chunk),
+                     (long long)a->ld_chunk * 2, a->Lc};
+    appended = a->mode != PAFU_MODE_SINGLE && !kv8 && compact_takes_tail(a->N * a->D * 2);
     rc = launch_compact(st, a->K_cache, a->V_cache, sel_scores, a->ld_cache * kvb, a->n, ids, n_kept, a->N * a->D * kvb,
-                        a->K_out, a->V_out, SL_out, a->ld_out * kvb);
+                        a->K_out, a->V_out, SL_out, a->ld_out * kvb, nullptr, appended ? &tail : nullptr);
     if (rc) return rc;
   }
   char* ko = static_cast<char*>(a->K_out) + (long long)n_kept * a->ld_out * kvb;
@@ -390,7 +396,7 @@ int enqueue_kv(hipStream_t st, const pafu_step_args* a, const int* ids, const fl
   if (rc) return rc;
   rc = record_stage(st, a, 4);
   if (rc) return rc;
-  if (a->mode != PAFU_MODE_SINGLE && !kv8) {
+  if (a->mode != PAFU_MODE_SINGLE && !kv8 && !appended) {
     rc = launch_append(st, a->K_chunk, a->V_chunk, nullptr, a->ld_chunk * 2, a->Lc, a->N * a->D * 2, ko, vo, nullptr,
                        a->ld_out * 2);
     if (rc) return rc;

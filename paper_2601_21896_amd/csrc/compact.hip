@@ -20,7 +20,7 @@ template <int CPL>  // 16-byte chunks per lane per row (row_bytes <= CPL*1024)
 __global__ __launch_bounds__(kCompactThreads) void compact_rows_kernel(
     const char* __restrict__ K, const char* __restrict__ V, const float* __restrict__ SL, long long ld_in, int n,
     const int* __restrict__ ids, int count, int chunks, char* __restrict__ Ko, char* __restrict__ Vo,
-    float* __restrict__ SLo, long long ld_out, const int* __restrict__ count_dev) {
+    float* __restrict__ SLo, long long ld_out, const int* __restrict__ count_dev, CompactTail tail) {
   const int lane = threadIdx.x & 63;
   const int wave = blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
   const int n_waves = gridDim.x * kWavesPerBlock;
@@ -28,11 +28,21 @@ __global__ __launch_bounds__(kCompactThreads) void compact_rows_kernel(
     const int c = *count_dev;
     count = c < count ? (c < 0 ? 0 : c) : count;
   }
-  for (int r = wave; r < count; r += n_waves) {
-    const int id = ids[r];
-    if ((unsigned)id >= (unsigned)n) continue;  // invalid index: leave the row untouched
-    const u32x4* ks = reinterpret_cast<const u32x4*>(K + (long long)id * ld_in);
-    const u32x4* vs = reinterpret_cast<const u32x4*>(V + (long long)id * ld_in);
+  // rows [0, count) are gathered through ids; rows [count, count + tail.rows) are the tail's rows in order (the
+  // chunk that a rollout appends behind the retained rows, Alg. 2)
+  const int total = count + tail.rows;
+  for (int r = wave; r < total; r += n_waves) {
+    const u32x4 *ks, *vs;
+    int id = 0;
+    if (r < count) {
+      id = ids[r];
+      if ((unsigned)id >= (unsigned)n) continue;  // invalid index: leave the row untouched
+      ks = reinterpret_cast<const u32x4*>(K + (long long)id * ld_in);
+      vs = reinterpret_cast<const u32x4*>(V + (long long)id * ld_in);
+    } else {
+      ks = reinterpret_cast<const u32x4*>(tail.K + (long long)(r - count) * tail.ld);
+      vs = reinterpret_cast<const u32x4*>(tail.V + (long long)(r - count) * tail.ld);
+    }
     u32x4* kd = reinterpret_cast<u32x4*>(Ko + (long long)r * ld_out);
     u32x4* vd = reinterpret_cast<u32x4*>(Vo + (long long)r * ld_out);
     u32x4 kb[CPL], vb[CPL];
@@ -52,7 +62,7 @@ __global__ __launch_bounds__(kCompactThreads) void compact_rows_kernel(
         __builtin_nontemporal_store(vb[i], vd + c);
       }
     }
-    if (SL != nullptr && lane == 0) SLo[r] = SL[id];
+    if (SL != nullptr && lane == 0 && r < count) SLo[r] = SL[id];
   }
 }
 
@@ -157,11 +167,19 @@ int grid_for_rows(int rows) {
 
 }  // namespace
 
+bool compact_takes_tail(int row_bytes) { return row_bytes % 16 == 0 && row_bytes <= kMaxChunksPerLane * 1024; }
+
 int launch_compact(hipStream_t st, const void* K, const void* V, const float* SL, long long ld_in_bytes, int n,
                    const int* ids, int count, int row_bytes, void* K_out, void* V_out, float* SL_out,
-                   long long ld_out_bytes, const int* count_dev) {
-  if (count <= 0) return PAFU_OK;
-  const dim3 grid(grid_for_rows(count)), block(kCompactThreads);
+                   long long ld_out_bytes, const int* count_dev, const CompactTail* tail_rows) {
+  CompactTail tail{nullptr, nullptr, 0, 0};
+  if (tail_rows != nullptr && tail_rows->rows > 0) {
+    if (!compact_takes_tail(row_bytes)) return PAFU_ERR_SHAPE;  // callers ask compact_takes_tail first
+    tail = *tail_rows;
+  }
+  if (count < 0) count = 0;
+  if (count + tail.rows <= 0) return PAFU_OK;
+  const dim3 grid(grid_for_rows(count + tail.rows)), block(kCompactThreads);
   const char* k = static_cast<const char*>(K);
   const char* v = static_cast<const char*>(V);
   char* ko = static_cast<char*>(K_out);
@@ -171,7 +189,7 @@ int launch_compact(hipStream_t st, const void* K, const void* V, const float* SL
     const int cpl = (chunks + 63) / 64;
 #define PAFU_COMPACT_CASE(C)                                                                                  \
   hipLaunchKernelGGL(compact_rows_kernel<C>, grid, block, 0, st, k, v, SL, ld_in_bytes, n, ids, count, chunks, \
-                     ko, vo, SL_out, ld_out_bytes, count_dev)
+                     ko, vo, SL_out, ld_out_bytes, count_dev, tail)
     if (cpl <= 1) PAFU_COMPACT_CASE(1);
     else if (cpl <= 2) PAFU_COMPACT_CASE(2);
     else if (cpl <= 3) PAFU_COMPACT_CASE(3);

@@ -38,9 +38,18 @@ inline bool overlaps(const void* a, size_t a_bytes, const void* b, size_t b_byte
 }
 
 // Stage launchers (validated arguments only).
+// Rows that the compaction copies, in order, behind the gathered ones (output rows count, count + 1, ...): the chunk
+// that a rollout appends to the compacted cache (Alg. 2), moved by the same launch.
+struct CompactTail {
+  const char* K;
+  const char* V;
+  long long ld;  // bytes between rows
+  int rows;
+};
+bool compact_takes_tail(int row_bytes);  // rows of whole 16-byte chunks, up to 12 KiB
 int launch_compact(hipStream_t st, const void* K, const void* V, const float* SL, long long ld_in_bytes, int n,
                    const int* ids, int count, int row_bytes, void* K_out, void* V_out, float* SL_out,
-                   long long ld_out_bytes, const int* count_dev = nullptr);
+                   long long ld_out_bytes, const int* count_dev = nullptr, const CompactTail* tail_rows = nullptr);
 // One layer of a batched compaction: its cache tensors, output slabs, index list and (optionally) score list.
 struct CompactLayer {
   const char* K;
