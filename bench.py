@@ -56,6 +56,9 @@ def parse():
                     help="S-MLP widths: the benchmark's (F = H, M from the config, 1 output) or App. A's "
                          "([Q|K|V] = 3H inputs, 1024 hidden, 12 outputs averaged)")
     ap.add_argument("--pinned", type=int, default=0, help="frame sink: cached tokens [0, pinned) are never evicted")
+    ap.add_argument("--graph", action="store_true",
+                    help="time replays of the step captured as a HIP graph (one graph per input set); the stage "
+                         "breakdown still comes from eager steps")
     ap.add_argument("--sustained-s", type=float, default=1.0,
                     help="length of the extra back-to-back run behind sustained_ms_per_step (0 = skip)")
     ap.add_argument("--chunk-frames", type=int, default=0, help="ATTN only: frames per chunk (default 3)")
@@ -386,6 +389,22 @@ def main():
         else:
             B.pafu_step_layers([s["args"] for s in sets])
 
+    run_step_eager = run_step
+    if a.graph:
+        # the library enqueues kernels only, so a step captures as it stands; one graph per rotated input set
+        run_step_eager(0)
+        torch.cuda.synchronize()
+        graphs = []
+        for i in range(n_sets if n_layers == 1 else 1):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                run_step_eager(i)
+            graphs.append(g)
+        torch.cuda.synchronize()
+
+        def run_step(i):
+            graphs[i % len(graphs)].replay()
+
     def timed_window(warmup, steps):
         """warmup untimed steps, then `steps` whole steps between two events with nothing else on the stream."""
         for i in range(warmup):
@@ -434,7 +453,7 @@ def main():
             step_evs.append(sev)
         eva, evb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         eva.record()
-        run_step(i)
+        run_step_eager(i)
         evb.record()
         recorded.append((eva, evb, step_evs))
     torch.cuda.synchronize()
@@ -600,6 +619,7 @@ def main():
                    "indices": "shared (last layer's head)" if shared else "per layer",
                    "n_pinned": a.pinned, "kv_storage": a.kv},
         "wall_ms_per_step": wall_ms,
+        "launch": "HIP graph replay" if a.graph else "eager",
         "first_window_ms_per_step": first_ms,
         "sustained_ms_per_step": sustained["ms_per_step"] if sustained else None,
         "sustained_steps": sustained["steps"] if sustained else None,

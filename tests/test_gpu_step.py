@@ -198,6 +198,15 @@ def test_rollout_full_budget_never_evicts():
     assert sizes == [40, 80, 120, 160, 200]
 
 
+@pytest.mark.parametrize("N,D", [(40, 128), (52, 128), (3, 64)])
+def test_rollout_row_sizes_on_both_sides_of_the_fused_append(N, D):
+    # rows of 10 KiB (appended by the compaction launch), 13 KiB (beyond the unrolled copy: generic compaction and a
+    # separate append) and 384 B; the oracle comparison inside _rollout covers the whole slab after every step
+    cfg = wl.scaled(wl.C1, N=N, D=D, M=32, frame_tokens=12, chunk_frames=2, cache_frames=0, k=60)     # Lc = 24
+    out, sizes = _rollout(cfg, 60, 6, cfg.Lc)
+    assert sizes == [24, 48, 72, 84, 84, 84]
+
+
 def test_rollout_with_frame_sink_keeps_the_first_frame():
     cfg = wl.scaled(wl.C1, frame_tokens=30, chunk_frames=3, cache_frames=0, k=240)     # Lc = 90
     first = wl.round_to_bf16(wl.make_chunk_inputs(cfg, 0)["K_chunk"])[:30]
