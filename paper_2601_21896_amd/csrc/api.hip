@@ -356,8 +356,10 @@ WsPart attention_ws(const pafu_step_args* a, bool scoring) {
 
 // The cache part of a step for one layer: compact K/V (and the score list when sel_scores is given) to `ids`,
 // attend over retained + chunk, and in ROLLOUT append the chunk's K/V behind the retained rows.
+// `done`: what a batched launch of the caller has already moved for this layer.
+enum : int { kDoneNothing = 0, kDoneCompact = 1, kDoneAppend = 2 };
 int enqueue_kv(hipStream_t st, const pafu_step_args* a, const int* ids, const float* sel_scores, float* SL_out,
-               void* attn_ws, size_t attn_ws_bytes, bool compacted = false) {
+               void* attn_ws, size_t attn_ws_bytes, int done = kDoneNothing) {
   const int n_kept = a->k < a->n ? a->k : a->n;
   const float scale = a->softmax_scale > 0.f ? a->softmax_scale : 1.0f / sqrtf((float)a->D);
   const bool kv8 = a->kv_dtype == PAFU_FP8_E4M3;
@@ -365,8 +367,8 @@ int enqueue_kv(hipStream_t st, const pafu_step_args* a, const int* ids, const fl
   int rc;
   // In a rollout with bf16 storage the compaction launch also moves the chunk's rows behind the retained ones: the
   // append costs no launch of its own, and attention (which reads the chunk from its own buffers) does not wait for it.
-  bool appended = false;
-  if (a->n > 0 && !compacted) {
+  bool appended = (done & kDoneAppend) != 0;
+  if (a->n > 0 && !(done & kDoneCompact)) {
     CompactTail tail{static_cast<const char*>(a->K_chunk), static_cast<const char*>(a->V_chunk),
                      (long long)a->ld_chunk * 2, a->Lc};
     appended = a->mode != PAFU_MODE_SINGLE && !kv8 && compact_takes_tail(a->N * a->D * 2);
@@ -419,20 +421,24 @@ int enqueue_step(hipStream_t st, const pafu_step_args* a) {
 }
 
 // Multi-layer steps: when all layers share the cache geometry their compactions run as one launch per 32 layers
-// (each layer with its own tensors and index list; `shared_ids` non-null = one list for all).  Returns whether it did.
-bool enqueue_compact_batch(hipStream_t st, const pafu_step_args* args, int n_layers, const int* shared_ids,
+// (each layer with its own tensors and index list; `shared_ids` non-null = one list for all).  In a bf16 rollout whose
+// layers also share the chunk geometry the same launch appends every layer's chunk rows.  Returns what it did
+// (kDone* bits).
+int enqueue_compact_batch(hipStream_t st, const pafu_step_args* args, int n_layers, const int* shared_ids,
                            int score_layer /* -1: every layer compacts its own score list */, int* rc_out) {
   *rc_out = PAFU_OK;
-  if (n_layers < 2) return false;
+  if (n_layers < 2) return kDoneNothing;
   const pafu_step_args* a0 = &args[0];
   const int kvb = kv_dtype_bytes(a0->kv_dtype);
   const long long rowb = (long long)a0->N * a0->D * kvb;
-  if (a0->n <= 0 || rowb > (1 << 20) || !compact_batchable((int)rowb)) return false;
+  if (a0->n <= 0 || rowb > (1 << 20) || !compact_batchable((int)rowb)) return kDoneNothing;
+  bool tail = a0->mode != PAFU_MODE_SINGLE && a0->kv_dtype == PAFU_BF16;
   for (int l = 1; l < n_layers; ++l) {
     const pafu_step_args* a = &args[l];
     if (a->n != a0->n || a->k != a0->k || a->N != a0->N || a->D != a0->D || a->kv_dtype != a0->kv_dtype ||
         a->ld_cache != a0->ld_cache || a->ld_out != a0->ld_out)
-      return false;
+      return kDoneNothing;
+    if (a->mode != a0->mode || a->Lc != a0->Lc || a->ld_chunk != a0->ld_chunk) tail = false;
   }
   const int n_kept = a0->k < a0->n ? a0->k : a0->n;
   CompactLayer layers[kCompactBatchMax];
@@ -445,12 +451,14 @@ bool enqueue_compact_batch(hipStream_t st, const pafu_step_args* args, int n_lay
       layers[i] = CompactLayer{static_cast<const char*>(a->K_cache), static_cast<const char*>(a->V_cache),
                                static_cast<char*>(a->K_out), static_cast<char*>(a->V_out),
                                shared_ids ? shared_ids : a->ids, with_scores ? sel : nullptr,
-                               with_scores ? a->SL_out : nullptr};
+                               with_scores ? a->SL_out : nullptr, static_cast<const char*>(a->K_chunk),
+                               static_cast<const char*>(a->V_chunk)};
     }
-    *rc_out = launch_compact_batch(st, layers, m, a0->ld_cache * kvb, a0->n, n_kept, (int)rowb, a0->ld_out * kvb);
-    if (*rc_out) return true;
+    *rc_out = launch_compact_batch(st, layers, m, a0->ld_cache * kvb, a0->n, n_kept, (int)rowb, a0->ld_out * kvb,
+                                   tail ? a0->Lc : 0, (long long)a0->ld_chunk * 2);
+    if (*rc_out) return kDoneCompact;
   }
-  return true;
+  return tail ? (kDoneCompact | kDoneAppend) : kDoneCompact;
 }
 
 // Validates the cache part of a layer that takes its indices from another layer.
@@ -718,13 +726,13 @@ int pafu_step_layers(void* stream, const pafu_step_args* args, int n_layers) {
     if (rc) return rc;
   }
   int rc_batch;
-  const bool compacted = enqueue_compact_batch(st, args, n_layers, nullptr, -1, &rc_batch);
+  const int done = enqueue_compact_batch(st, args, n_layers, nullptr, -1, &rc_batch);
   if (rc_batch) return rc_batch;
   for (int l = 0; l < n_layers; ++l) {
     const pafu_step_args* a = &args[l];
     const WsPart ws = attention_ws(a, true);
     int rc = enqueue_kv(st, a, a->ids, a->mode == PAFU_MODE_SINGLE ? a->scores : a->SL_in, a->SL_out, ws.p, ws.bytes,
-                        compacted);
+                        done);
     if (rc) return rc;
   }
   return PAFU_OK;
@@ -758,7 +766,7 @@ int pafu_step_layers_shared(void* stream, const pafu_step_args* args, int n_laye
   // every layer's cache is compacted to the one index list in one launch (per 32 layers) when the layers share the
   // cache geometry, otherwise layer by layer
   int rc_batch;
-  const bool compacted = enqueue_compact_batch(st, args, n_layers, idx->ids, index_layer, &rc_batch);
+  const int done = enqueue_compact_batch(st, args, n_layers, idx->ids, index_layer, &rc_batch);
   if (rc_batch) return rc_batch;
   for (int l = 0; l < n_layers; ++l) {
     const bool is_idx = l == index_layer;
@@ -766,7 +774,7 @@ int pafu_step_layers_shared(void* stream, const pafu_step_args* args, int n_laye
     WsPart ws = attention_ws(&args[l], is_idx);
     if (ws.p == nullptr) ws = attention_ws(idx, true);
     rc = enqueue_kv(st, &args[l], idx->ids, is_idx ? sel_scores : nullptr, is_idx ? idx->SL_out : nullptr, ws.p,
-                    ws.bytes, compacted);
+                    ws.bytes, done);
     if (rc) return rc;
   }
   return PAFU_OK;

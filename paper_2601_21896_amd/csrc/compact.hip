@@ -72,18 +72,27 @@ __global__ __launch_bounds__(kCompactThreads) void compact_rows_kernel(
 template <int CPL>
 __global__ __launch_bounds__(kCompactThreads) void compact_rows_batch_kernel(CompactBatch B, int n_layers,
                                                                              long long ld_in, int n, int count,
-                                                                             int chunks, long long ld_out) {
+                                                                             int chunks, long long ld_out,
+                                                                             int tail_rows, long long ld_tail) {
   const int lane = threadIdx.x & 63;
   const int wave = blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
   const int n_waves = gridDim.x * kWavesPerBlock;
-  for (int r = wave; r < count; r += n_waves) {
+  const int total = count + tail_rows;  // rows [count, total) come from every layer's tail tensors, in order
+  for (int r = wave; r < total; r += n_waves) {
 #pragma unroll 1
     for (int l = 0; l < n_layers; ++l) {
       const CompactLayer& L = B.layer[l];
-      const int id = L.ids[r];
-      if ((unsigned)id >= (unsigned)n) continue;  // invalid index: leave the row untouched
-      const u32x4* ks = reinterpret_cast<const u32x4*>(L.K + (long long)id * ld_in);
-      const u32x4* vs = reinterpret_cast<const u32x4*>(L.V + (long long)id * ld_in);
+      const u32x4 *ks, *vs;
+      int id = 0;
+      if (r < count) {
+        id = L.ids[r];
+        if ((unsigned)id >= (unsigned)n) continue;  // invalid index: leave the row untouched
+        ks = reinterpret_cast<const u32x4*>(L.K + (long long)id * ld_in);
+        vs = reinterpret_cast<const u32x4*>(L.V + (long long)id * ld_in);
+      } else {
+        ks = reinterpret_cast<const u32x4*>(L.Kt + (long long)(r - count) * ld_tail);
+        vs = reinterpret_cast<const u32x4*>(L.Vt + (long long)(r - count) * ld_tail);
+      }
       u32x4* kd = reinterpret_cast<u32x4*>(L.Ko + (long long)r * ld_out);
       u32x4* vd = reinterpret_cast<u32x4*>(L.Vo + (long long)r * ld_out);
       u32x4 kb[CPL], vb[CPL];
@@ -103,7 +112,7 @@ __global__ __launch_bounds__(kCompactThreads) void compact_rows_batch_kernel(Com
           __builtin_nontemporal_store(vb[i], vd + c);
         }
       }
-      if (L.SL != nullptr && lane == 0) L.SLo[r] = L.SL[id];
+      if (L.SL != nullptr && lane == 0 && r < count) L.SLo[r] = L.SL[id];
     }
   }
 }
@@ -212,18 +221,20 @@ int launch_compact(hipStream_t st, const void* K, const void* V, const float* SL
 bool compact_batchable(int row_bytes) { return row_bytes % 16 == 0 && row_bytes <= 4 * 1024; }
 
 int launch_compact_batch(hipStream_t st, const CompactLayer* layers, int n_layers, long long ld_in_bytes, int n,
-                         int count, int row_bytes, long long ld_out_bytes) {
-  if (count <= 0 || n_layers <= 0) return PAFU_OK;
+                         int count, int row_bytes, long long ld_out_bytes, int tail_rows, long long ld_tail_bytes) {
+  if (count < 0) count = 0;
+  if (tail_rows < 0) tail_rows = 0;
+  if (count + tail_rows <= 0 || n_layers <= 0) return PAFU_OK;
   const int chunks = row_bytes / 16;
   const int cpl = (chunks + 63) / 64;
   for (int first = 0; first < n_layers; first += kCompactBatchMax) {
     const int m = n_layers - first < kCompactBatchMax ? n_layers - first : kCompactBatchMax;
     CompactBatch B;
     for (int i = 0; i < kCompactBatchMax; ++i) B.layer[i] = layers[first + (i < m ? i : 0)];
-    const dim3 grid(grid_for_rows(count)), block(kCompactThreads);
+    const dim3 grid(grid_for_rows(count + tail_rows)), block(kCompactThreads);
 #define PAFU_COMPACT_BATCH_CASE(C)                                                                                \
   hipLaunchKernelGGL(compact_rows_batch_kernel<C>, grid, block, 0, st, B, m, ld_in_bytes, n, count, chunks,      \
-                     ld_out_bytes)
+                     ld_out_bytes, tail_rows, ld_tail_bytes)
     if (cpl <= 1) PAFU_COMPACT_BATCH_CASE(1);
     else if (cpl <= 2) PAFU_COMPACT_BATCH_CASE(2);
     else if (cpl <= 3) PAFU_COMPACT_BATCH_CASE(3);

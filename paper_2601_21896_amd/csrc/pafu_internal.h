@@ -59,6 +59,8 @@ struct CompactLayer {
   const int* ids;
   const float* SL;  // null: no score list for this layer
   float* SLo;
+  const char* Kt;   // rows copied in order behind the gathered ones (the chunk a rollout appends); unused when the
+  const char* Vt;   // launch has no tail rows
 };
 constexpr int kCompactBatchMax = 32;  // layers per launch (they travel as kernel arguments)
 struct CompactBatch {
@@ -68,7 +70,8 @@ struct CompactBatch {
 bool compact_batchable(int row_bytes);
 // The layers share n, count, the row size and both strides.
 int launch_compact_batch(hipStream_t st, const CompactLayer* layers, int n_layers, long long ld_in_bytes, int n,
-                         int count, int row_bytes, long long ld_out_bytes);
+                         int count, int row_bytes, long long ld_out_bytes, int tail_rows = 0,
+                         long long ld_tail_bytes = 0);
 int launch_append(hipStream_t st, const void* K, const void* V, const float* S, long long ld_in_bytes, int rows,
                   int row_bytes, void* K_out, void* V_out, float* S_out, long long ld_out_bytes);
 // One top-k selection: scores [n] -> the min(k, n) retained indices, ascending (out_count may be null).

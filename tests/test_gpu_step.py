@@ -290,3 +290,47 @@ def test_step_layers_shared_rollout():
         assert np.array_equal(host(slabs[idx][1 - cur]["SL"][:n]), states[idx].SL), t
         cur = 1 - cur
     assert n == k + Lc
+
+
+def test_step_layers_rollout_independent_indices():
+    # pafu_step_layers in ROLLOUT: every layer scores its own chunk, selects on its own stored list, and the one
+    # compaction launch also appends every layer's chunk rows; each layer against its own oracle rollout
+    cfg = wl.scaled(wl.C1, frame_tokens=30, chunk_frames=2, cache_frames=0, k=150)      # Lc = 60
+    N, D, Lc, k, n_layers = cfg.N, cfg.D, cfg.Lc, 150, 3
+    W1, b1, W2, b2 = wl.make_rollout_weights(cfg, bias=True)
+    dW = (dev(W1, "bf16"), dev(b1), dev(W2), dev(b2))
+    cap = k + Lc
+    slabs = [[dict(K=torch.zeros(cap, N, D, device=DEV, dtype=torch.bfloat16),
+                   V=torch.zeros(cap, N, D, device=DEV, dtype=torch.bfloat16),
+                   SL=torch.zeros(cap, device=DEV)) for _ in range(2)] for _ in range(n_layers)]
+    states = [orc.RolloutState(N, D, np.float32) for _ in range(n_layers)]
+    ids = [torch.empty(k, dtype=torch.int32, device=DEV) for _ in range(n_layers)]
+    Os = [torch.empty(Lc, N, D, device=DEV, dtype=torch.bfloat16) for _ in range(n_layers)]
+    n, cur = 0, 0
+    for t in range(5):
+        chunks = [wl.make_chunk_inputs(cfg, 10 * t + l) for l in range(n_layers)]
+        n_kept = min(k, n)
+        args = []
+        for l in range(n_layers):
+            src, dst, c = slabs[l][cur], slabs[l][1 - cur], chunks[l]
+            args.append(B.make_step_args(
+                B.PAFU_MODE_ROLLOUT, N, D, n, Lc, k, Lc, None, dev(c["X_chunk"], "bf16"), dW[0], dW[1], dW[2], dW[3],
+                src["K"], src["V"], src["SL"], dev(c["Q"], "bf16"), dev(c["K_chunk"], "bf16"),
+                dev(c["V_chunk"], "bf16"), None, ids[l], dst["K"], dst["V"], dst["SL"], Os[l]))
+        B.pafu_step_layers(args)
+        torch.cuda.synchronize()
+        for l in range(n_layers):
+            dst, c = slabs[l][1 - cur], chunks[l]
+            s_chunk = host(dst["SL"][n_kept:n_kept + Lc])
+            out = orc.rollout_step(states[l], c["X_chunk"], W1, b1, W2, b2, c["Q"], c["K_chunk"], c["V_chunk"], k, Lc,
+                                   forced_chunk_scores_f32=s_chunk)
+            assert np.abs(s_chunk - out["s_chunk"]).max() < SCORE_MAX_ABS
+            assert np.array_equal(host(ids[l])[:n_kept], out["ids"]), (t, l)
+            m = n_kept + Lc
+            assert np.array_equal(host(dst["K"][:m]), states[l].K) and np.array_equal(host(dst["V"][:m]), states[l].V), (t, l)
+            assert np.array_equal(host(dst["SL"][:m]), states[l].SL), (t, l)
+            max_abs, rel = attn_errors(host(Os[l]), out["O"])
+            assert max_abs < ATTN_MAX_ABS and rel < ATTN_REL_FRO, (t, l, max_abs, rel)
+        n = n_kept + Lc
+        cur = 1 - cur
+    assert n == k + Lc
