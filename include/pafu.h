@@ -271,7 +271,9 @@ typedef struct pafu_step_args {
   int n_pinned;        /* frame sink: cached tokens [0, n_pinned) are never evicted (0 = none) */
   /* Optional timing hooks (host handles, hipEvent_t passed as void*, each NULL = not recorded): recorded on the
    * step's stream before scoring [0], after scoring [1], after selection [2], after compaction [3] and after
-   * attention [4] (ROLLOUT: the chunk rows are appended by the compaction launch, i.e. inside [2]..[3]; only when the
+   * attention [4] (ROLLOUT: the selection reads the stored list only and is done by one workgroup of the scoring
+   * launch when that launch is a short streaming one and the list holds at most 65536 scores, so [1]..[2] is then
+   * empty; the chunk rows are appended by the compaction launch, i.e. inside [2]..[3]; only when the
    * cache was empty, or the rows do not fit that kernel, a separate copy follows [4]).  In the multi-layer steps, whose stages are reordered across
    * layers, [0]/[1] bracket a layer's scoring and [3]/[4] its attention launch; [2] is recorded once, after the
    * selection launch, on args[0] (pafu_step_layers) or on the index layer (pafu_step_layers_shared). */

@@ -309,7 +309,10 @@ int check_step(const pafu_step_args* a) {
 
 // The scoring part of a step: SINGLE scores cache + chunk into a->scores, ROLLOUT the chunk into SL_out behind the
 // retained rows.
-int enqueue_scores(hipStream_t st, const pafu_step_args* a) {
+// `selected` (may be null): in ROLLOUT the selection reads the stored list only, so it may ride in the scoring launch;
+// set when it did and the caller has no selection left to launch.
+int enqueue_scores(hipStream_t st, const pafu_step_args* a, bool* selected = nullptr) {
+  if (selected != nullptr) *selected = false;
   const int n_kept = a->k < a->n ? a->k : a->n;
   const bool single = a->mode == PAFU_MODE_SINGLE;
   int rc = record_stage(st, a, 0);
@@ -336,8 +339,11 @@ int enqueue_scores(hipStream_t st, const pafu_step_args* a) {
     }
   } else {
     // SINGLE with an empty cache, or ROLLOUT (the chunk's scores land behind the retained ones in SL_out)
+    const SelectJob job{a->SL_in, a->ids, nullptr, a->n, a->k, a->n_pinned};
+    const bool may_ride = selected != nullptr && !single && a->n > 0;
     rc = launch_score(st, a->x_chunk[0], a->x_chunk[1], a->x_chunk[2], a->n_seg, a->Lc, a->Fs, a->ld_x, a->x_dtype,
-                      a->W1, a->b1, a->W2, a->b2, a->M, a->n_out, a->act, chunk_scores, a->workspace);
+                      a->W1, a->b1, a->W2, a->b2, a->M, a->n_out, a->act, chunk_scores, a->workspace,
+                      may_ride ? &job : nullptr, selected);
     if (rc) return rc;
   }
   return record_stage(st, a, 1);
@@ -407,10 +413,11 @@ int enqueue_kv(hipStream_t st, const pafu_step_args* a, const int* ids, const fl
 }
 
 int enqueue_step(hipStream_t st, const pafu_step_args* a) {
-  int rc = enqueue_scores(st, a);
+  bool selected = false;
+  int rc = enqueue_scores(st, a, &selected);
   if (rc) return rc;
   const float* sel_scores = a->mode == PAFU_MODE_SINGLE ? a->scores : a->SL_in;
-  if (a->n > 0) {
+  if (a->n > 0 && !selected) {
     rc = launch_select(st, sel_scores, a->n, a->k, a->n_pinned, a->ids, nullptr, nullptr);
     if (rc) return rc;
   }
@@ -754,10 +761,11 @@ int pafu_step_layers_shared(void* stream, const pafu_step_args* args, int n_laye
   hipStream_t st = static_cast<hipStream_t>(stream);
   // ROLLOUT selects on the stored list, so the indices exist before any layer runs; the chunk's own scores are only
   // needed for the append.  SINGLE scores first.  Either way: scores, one selection, then every layer's cache.
-  rc = enqueue_scores(st, idx);
+  bool selected = false;
+  rc = enqueue_scores(st, idx, &selected);
   if (rc) return rc;
   const float* sel_scores = idx->mode == PAFU_MODE_SINGLE ? idx->scores : idx->SL_in;
-  if (idx->n > 0) {
+  if (idx->n > 0 && !selected) {
     rc = launch_select(st, sel_scores, idx->n, idx->k, idx->n_pinned, idx->ids, nullptr, nullptr);
     if (rc) return rc;
   }

@@ -90,7 +90,11 @@ int launch_select(hipStream_t st, const float* scores, int n, int k, int n_pinne
                   void* ws);
 int launch_score(hipStream_t st, const void* x0, const void* x1, const void* x2, int n_seg, int T, int Fs,
                  long long ld_x, int x_dtype, const void* W1, const float* b1, const float* W2, const float* b2,
-                 int M, int n_out, int act, float* out, void* ws);
+                 int M, int n_out, int act, float* out, void* ws, const SelectJob* ride = nullptr,
+                 bool* rode = nullptr);
+// `ride`: a selection that does not depend on these scores (the stored list of a rollout step); when the launch is a
+// short streaming one it is done by one extra workgroup of the same launch and *rode is set, otherwise the caller
+// launches it.
 // The same with the folded second layer in the library's own static device array (no workspace, no allocation).
 int launch_score_static(hipStream_t st, const void* x0, const void* x1, const void* x2, int n_seg, int T, int Fs,
                         long long ld_x, int x_dtype, const void* W1, const float* b1, const float* W2,

@@ -17,6 +17,7 @@
 //
 // generic path (fp32 inputs, or shapes the tiles do not divide): plain fp32 FMAs.
 #include "pafu_internal.h"
+#include "select_body.h"
 
 namespace pafu {
 namespace {
@@ -259,11 +260,22 @@ __device__ __forceinline__ void s3_wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
-template <int TT>
+// SELW > 0: workgroup 0 of the launch does not score but runs a top-k selection (SELW key words per thread, 512
+// threads) on a list that does not depend on this launch's scores: the stored score list of a rollout step.  A
+// selection keeps one CU busy for about as long as the scoring of a chunk takes the others, so carried along it
+// costs nothing, where a launch of its own would leave the rest of the chip idle meanwhile.
+template <int TT, int SELW>
 __global__ __launch_bounds__(512, 1) void score_stream_kernel(
     const unsigned short* __restrict__ x0, const unsigned short* __restrict__ x1, const unsigned short* __restrict__ x2,
     int T, int Fs, int F, long long ld_x, const unsigned short* __restrict__ W1, const float* __restrict__ b1,
-    const float* __restrict__ w2bar, const float* __restrict__ b2bar, int M, int act, float* __restrict__ out) {
+    const float* __restrict__ w2bar, const float* __restrict__ b2bar, int M, int act, float* __restrict__ out,
+    SelectJob ride) {
+  if constexpr (SELW > 0) {
+    if (blockIdx.x == 0) {
+      select_bitslice_body<SELW, 512>(ride);
+      return;
+    }
+  }
   constexpr int kStageB = s3_stage_bytes(TT);
   constexpr int WU = 256 / kS3RowsPerLoad;             // wave-wide loads that fill the W1 part of a stage
   constexpr int XU = 32 * TT / kS3RowsPerLoad;         // ... and the feature part
@@ -282,7 +294,7 @@ __global__ __launch_bounds__(512, 1) void score_stream_kernel(
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // said to be uniform: LDS addresses of the loads stay scalar
   const int hq = wave & 3, kh = wave >> 2;
   const int g = lane >> 5, c = lane & 31;
-  const int tok_base = blockIdx.x * (32 * TT);
+  const int tok_base = (blockIdx.x - (SELW > 0 ? 1 : 0)) * (32 * TT);
   const int n_slabs = F / kS3Slab;
   const int slabs_per_seg = Fs / kS3Slab;
 
@@ -506,7 +518,8 @@ int launch_score_static(hipStream_t st, const void* x0, const void* x1, const vo
 
 int launch_score(hipStream_t st, const void* x0, const void* x1, const void* x2, int n_seg, int T, int Fs,
                  long long ld_x, int x_dtype, const void* W1, const float* b1, const float* W2, const float* b2, int M,
-                 int n_out, int act, float* out, void* ws) {
+                 int n_out, int act, float* out, void* ws, const SelectJob* ride, bool* rode) {
+  if (rode != nullptr) *rode = false;
   if (T <= 0) return PAFU_OK;
   const float* w2bar = W2;
   const float* b2bar = b2;
@@ -549,16 +562,32 @@ int launch_score(hipStream_t st, const void* x0, const void* x1, const void* x2,
         const long long cost = (long long)((wgs + 255) / 256) * ((kS3Slab / 32) * (mfma > lds ? mfma : lds) + 100);
         if (cost <= best_cost) { best_cost = cost; best_tt = tt; }
       }
-#define PAFU_SCORE3_CASE(TT)                                                                                         \
+#define PAFU_SCORE3_LAUNCH(TT, SELW, LDS, EXTRA)                                                                     \
   do {                                                                                                               \
     static LdsLimit lds_limit3;                                                                                      \
-    const int rc_ = set_lds_limit(lds_limit3, score_stream_kernel<TT>, s3_lds_bytes(TT));                            \
+    const int rc_ = set_lds_limit(lds_limit3, score_stream_kernel<TT, SELW>, LDS);                                   \
     if (rc_ != PAFU_OK) return rc_;                                                                                  \
-    hipLaunchKernelGGL(score_stream_kernel<TT>, dim3((tiles + TT - 1) / TT), dim3(512), s3_lds_bytes(TT), st,        \
+    hipLaunchKernelGGL((score_stream_kernel<TT, SELW>), dim3((tiles + TT - 1) / TT + EXTRA), dim3(512), LDS, st,     \
                        static_cast<const unsigned short*>(x0), static_cast<const unsigned short*>(x1),               \
                        static_cast<const unsigned short*>(x2), T, Fs, F, ld_x, static_cast<const unsigned short*>(W1), \
-                       b1, w2bar, b2bar, M, act, out);                                                               \
+                       b1, w2bar, b2bar, M, act, out, job);                                                          \
   } while (0)
+#define PAFU_SCORE3_CASE(TT) PAFU_SCORE3_LAUNCH(TT, 0, s3_lds_bytes(TT), 0)
+#define PAFU_SCORE3_RIDE(TT, SELW)                                                                                   \
+  PAFU_SCORE3_LAUNCH(TT, SELW,                                                                                       \
+                     (s3_lds_bytes(TT) > select_bitslice_lds_bytes(512) ? s3_lds_bytes(TT) : select_bitslice_lds_bytes(512)), 1)
+      SelectJob job{nullptr, nullptr, nullptr, 0, 0, 0};
+      // a selection rides along when the launch is short (one or two token tiles per workgroup: a chunk, not a whole
+      // cache) and the list fits the 512-thread bit-sliced selection
+      if (ride != nullptr && best_tt <= 2 && ride->n > 0 && ride->n <= 512 * 32 * 4) {
+        job = *ride;
+        if (job.n_pinned < 0) job.n_pinned = 0;
+        const bool w2 = job.n <= 512 * 32 * 2;
+        if (best_tt == 1) { if (w2) PAFU_SCORE3_RIDE(1, 2); else PAFU_SCORE3_RIDE(1, 4); }
+        else { if (w2) PAFU_SCORE3_RIDE(2, 2); else PAFU_SCORE3_RIDE(2, 4); }
+        if (rode != nullptr) *rode = true;
+        return check_launch();
+      }
       switch (best_tt) {
         case 1: PAFU_SCORE3_CASE(1); break;
         case 2: PAFU_SCORE3_CASE(2); break;
@@ -567,6 +596,8 @@ int launch_score(hipStream_t st, const void* x0, const void* x1, const void* x2,
         default: PAFU_SCORE3_CASE(5); break;
       }
 #undef PAFU_SCORE3_CASE
+#undef PAFU_SCORE3_RIDE
+#undef PAFU_SCORE3_LAUNCH
     } else if (blocks % 8 == 0) PAFU_SCORE_CASE(8);
     else if (blocks % 4 == 0) PAFU_SCORE_CASE(4);
     else if (blocks % 2 == 0) PAFU_SCORE_CASE(2);
