@@ -256,6 +256,9 @@ def rollout(a, torch, np, B, wl):
         "min_ms": float(np.min(steady)), "first_steps_ms": [float(x) for x in times[:5]], "cache_sizes_first_steps": sizes[:6],
         "peak_cache_bytes": peak_cache,
         "stages": {s: {"ms": float(np.mean(st[:, j])), "min_ms": float(np.min(st[:, j]))} for j, s in enumerate(stage_names)},
+        "stage_note": "ROLLOUT: the selection on the stored list is done by one workgroup of the scoring launch (lists up "
+                      "to 65536 scores), so the interval after scoring is empty; the compaction launch also appends the "
+                      "chunk's rows (bf16) / is followed by the chunk's quantisation (8-bit), both inside 'compact'",
         "compact_bytes": bytes_compact,
         "compact_GB/s": bytes_compact / float(np.mean(st[:, 2])) / 1e6 if n_kept else None,
         "roofline": {"kernel": "chunk_attention_kernel", "bound": "mfma", "achieved": flops / attn_ms / 1e9,
