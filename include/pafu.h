@@ -156,7 +156,8 @@ int pafu_compact_kv_counted(void* stream, const void* K, const void* V, const fl
  *   Q  : [Lq, N, D] bf16, stride ld_q      Kc,Vc : [n_kept, N, D] bf16, stride ld_c (may be NULL if n_kept == 0)
  *   Kn,Vn : [Lc, N, D] bf16, stride ld_n   O : [Lq, N, D] of out_dtype (bf16 or fp32), stride ld_o
  *   softmax_scale <= 0 means 1/sqrt(D).    D must be 64 or 128.  Lq >= 1, Lc >= 1, block_len >= 1.
- *   Query i is chunk token i (Lq <= Lc on this path).
+ *   Query i is chunk token i (Lq <= Lc on this path).  The tensors may be of any size, but 64 consecutive K/V rows
+ *   must span less than 4 GiB (ld_c, ld_n below 2^25 elements), else PAFU_ERR_SHAPE.
  *   workspace : optional (NULL / 0 allowed).  With pafu_attention_workspace_bytes(Lq, N, D) bytes (16-byte aligned,
  *               apart from every tensor of the call) a launch whose (head, 256-query tile) items would fill at most
  *               four fifths of the GPU's compute units cuts its work into equal runs over the key axis, one per

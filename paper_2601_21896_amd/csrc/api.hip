@@ -100,6 +100,8 @@ int check_attention(const void* Q, int Lq, const void* Kc, const void* Vc, int n
   if (ob == 0) return PAFU_ERR_DTYPE;
   const long long row = (long long)N * D;
   if (ld_q < row || ld_n < row || ld_o < row || (n_kept > 0 && ld_c < row)) return PAFU_ERR_SHAPE;
+  // a 64-key tile is addressed as a 64-bit tile base plus 32-bit byte offsets: 64 rows must span less than 4 GiB
+  if (ld_n * kvb * 64 >= (1ll << 32) || (n_kept > 0 && ld_c * kvb * 64 >= (1ll << 32))) return PAFU_ERR_SHAPE;
   if (!Q || !Kn || !Vn || !O || (n_kept > 0 && (!Kc || !Vc))) return PAFU_ERR_NULL;
   if (!aligned16(Q) || !aligned16(Kn) || !aligned16(Vn) || !aligned16(O) || !aligned16(Kc) || !aligned16(Vc) ||
       (ld_q * 2) % 16 != 0 || (ld_n * kvb) % 16 != 0 || (ld_c * kvb) % 16 != 0 || (ld_o * ob) % 16 != 0)

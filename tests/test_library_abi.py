@@ -197,6 +197,17 @@ def test_step_rejects_aliased_buffers():
     assert lib.pafu_step_layers_shared(None, pair, 2, 1) == -6
 
 
+def test_attention_rejects_row_strides_its_tile_offsets_cannot_hold():
+    f = binding.library().pafu_chunk_attention
+
+    def call(ld_c=256, ld_n=256, n_kept=100):
+        return f(None, A, 64, A + 0x10000000, A + 0x20000000, n_kept, A + 0x30000000, A + 0x40000000, 64, 2, 128, 256,
+                 ld_c, ld_n, 256, 64, 0.0, A + 0x50000000, 0, None, 0)
+    assert call(ld_c=(1 << 25)) == -2
+    assert call(ld_n=(1 << 25)) == -2
+    assert call(ld_c=(1 << 25) - 8, n_kept=1) in (0, -7)       # accepted (a launch error without a GPU)
+
+
 def test_new_entry_points_reject_bad_arguments():
     lib = binding.library()
     # pafu_score_static: same checks as pafu_score, plus the limit of its static scratch
