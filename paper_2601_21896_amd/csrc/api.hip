@@ -377,16 +377,18 @@ int enqueue_kv(hipStream_t st, const pafu_step_args* a, const int* ids, const fl
   // append costs no launch of its own, and attention (which reads the chunk from its own buffers) does not wait for it.
   bool appended = (done & kDoneAppend) != 0;
   if (a->n > 0 && !(done & kDoneCompact)) {
+    // (with the 8-bit cache the tail rows are quantised on the way, in both modes: the chunk always attends over codes)
     CompactTail tail{static_cast<const char*>(a->K_chunk), static_cast<const char*>(a->V_chunk),
-                     (long long)a->ld_chunk * 2, a->Lc};
-    appended = a->mode != PAFU_MODE_SINGLE && !kv8 && compact_takes_tail(a->N * a->D * 2);
+                     (long long)a->ld_chunk * 2, a->Lc, kv8 ? 1 : 0, ldexpf(1.0f, -a->k_scale_log2),
+                     ldexpf(1.0f, -a->v_scale_log2)};
+    appended = (kv8 || a->mode != PAFU_MODE_SINGLE) && compact_takes_tail(a->N * a->D * kvb);
     rc = launch_compact(st, a->K_cache, a->V_cache, sel_scores, a->ld_cache * kvb, a->n, ids, n_kept, a->N * a->D * kvb,
                         a->K_out, a->V_out, SL_out, a->ld_out * kvb, nullptr, appended ? &tail : nullptr);
     if (rc) return rc;
   }
   char* ko = static_cast<char*>(a->K_out) + (long long)n_kept * a->ld_out * kvb;
   char* vo = static_cast<char*>(a->V_out) + (long long)n_kept * a->ld_out * kvb;
-  if (kv8) {
+  if (kv8 && !appended) {
     // the chunk's K/V enter the cache as codes before attention: the chunk attends over exactly what later steps
     // will find in the cache, and in a rollout nothing is left to append
     rc = launch_quantize(st, a->K_chunk, a->V_chunk, a->ld_chunk * 2, a->Lc, a->N * a->D, a->k_scale_log2,

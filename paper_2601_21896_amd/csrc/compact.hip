@@ -6,6 +6,7 @@
 // evicted rows are never touched.  One wave moves one row of K and the same row of V per iteration,
 // with all of a row's loads issued before its stores so that several KiB per wave are in flight.
 #include "pafu_internal.h"
+#include "quant_body.h"
 
 namespace pafu {
 namespace {
@@ -45,6 +46,27 @@ __global__ __launch_bounds__(kCompactThreads) void compact_rows_kernel(
     }
     u32x4* kd = reinterpret_cast<u32x4*>(Ko + (long long)r * ld_out);
     u32x4* vd = reinterpret_cast<u32x4*>(Vo + (long long)r * ld_out);
+    if (r >= count && tail.quant) {  // wave-uniform: 16 codes per lane and tensor from 32 bytes of bf16
+#pragma unroll
+      for (int i = 0; i < CPL; ++i) {
+        const int c = lane + 64 * i;
+        if (c < chunks) {
+#pragma unroll
+          for (int t = 0; t < 2; ++t) {
+            const u32x4* src = (t ? vs : ks) + 2 * c;
+            const u32x4 lo = __builtin_nontemporal_load(src), hi = __builtin_nontemporal_load(src + 1);
+            const unsigned wl[4] = {lo[0], lo[1], lo[2], lo[3]}, wh[4] = {hi[0], hi[1], hi[2], hi[3]};
+            unsigned cl[2], ch[2];
+            e4m3_codes8(wl, t ? tail.inv_v : tail.inv_k, cl);
+            e4m3_codes8(wh, t ? tail.inv_v : tail.inv_k, ch);
+            u32x4 o;
+            o[0] = cl[0]; o[1] = cl[1]; o[2] = ch[0]; o[3] = ch[1];
+            __builtin_nontemporal_store(o, (t ? vd : kd) + c);
+          }
+        }
+      }
+      continue;
+    }
     u32x4 kb[CPL], vb[CPL];
 #pragma unroll
     for (int i = 0; i < CPL; ++i) {
@@ -181,7 +203,7 @@ bool compact_takes_tail(int row_bytes) { return row_bytes % 16 == 0 && row_bytes
 int launch_compact(hipStream_t st, const void* K, const void* V, const float* SL, long long ld_in_bytes, int n,
                    const int* ids, int count, int row_bytes, void* K_out, void* V_out, float* SL_out,
                    long long ld_out_bytes, const int* count_dev, const CompactTail* tail_rows) {
-  CompactTail tail{nullptr, nullptr, 0, 0};
+  CompactTail tail{nullptr, nullptr, 0, 0, 0, 1.f, 1.f};
   if (tail_rows != nullptr && tail_rows->rows > 0) {
     if (!compact_takes_tail(row_bytes)) return PAFU_ERR_SHAPE;  // callers ask compact_takes_tail first
     tail = *tail_rows;

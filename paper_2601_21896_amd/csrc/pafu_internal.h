@@ -45,6 +45,10 @@ struct CompactTail {
   const char* V;
   long long ld;  // bytes between rows
   int rows;
+  // quant != 0: the tail rows are bf16 and the output rows 8-bit codes (E4M3 of value * inv_k / inv_v): the chunk of a
+  // step with the 8-bit cache, quantised behind the retained codes by the same launch
+  int quant;
+  float inv_k, inv_v;
 };
 bool compact_takes_tail(int row_bytes);  // rows of whole 16-byte chunks, up to 12 KiB
 int launch_compact(hipStream_t st, const void* K, const void* V, const float* SL, long long ld_in_bytes, int n,

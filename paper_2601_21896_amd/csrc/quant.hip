@@ -6,34 +6,13 @@
 // (the cache must match a reference bit for bit); the way back uses the hardware's 8-bit -> bf16 conversion, which is
 // exact for every code and scale.
 #include "pafu_internal.h"
+#include "quant_body.h"
 
 namespace pafu {
 namespace {
 
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
-
-// x * inv_scale (exact: inv_scale is a power of two) -> E4M3 code
-__device__ __forceinline__ unsigned e4m3_code(float x, float inv_scale) {
-  const float v = x * inv_scale;
-  const unsigned u = __float_as_uint(v);
-  const unsigned sign = (u >> 24) & 0x80u;
-  const unsigned au = u & 0x7fffffffu;
-  if (au > 0x7f800000u) return sign | 0x7fu;  // NaN
-  const float a = fminf(__uint_as_float(au), 448.0f);
-  unsigned code;
-  if (a < 0.015625f) {  // below the smallest normal 2^-6: the grid is k * 2^-9, k = 0..8 (8 = the smallest normal)
-    code = (unsigned)__builtin_rintf(a * 512.0f);
-  } else {
-    unsigned b = __float_as_uint(a);
-    b += 0x7ffffu + ((b >> 20) & 1u);        // nearest even at 3 mantissa bits (a carry moves into the exponent)
-    code = ((b >> 20) & 0x7ffu) - (120u << 3);  // exponent bias 127 -> 7
-  }
-  return sign | code;
-}
-
-__device__ __forceinline__ float bf16_lo(unsigned w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float bf16_hi(unsigned w) { return __uint_as_float(w & 0xffff0000u); }
 
 // One thread = 8 elements (16 bytes in, 8 bytes out) of K and of V.
 __global__ __launch_bounds__(256) void quantize_rows_kernel(const char* __restrict__ K, const char* __restrict__ V,
@@ -49,12 +28,12 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const char* __restri
       char* dst = (t ? Vq : Kq) + (long long)r * ld_out + c * 8;
       const float inv = t ? inv_v : inv_k;
       const u32x4 w = *reinterpret_cast<const u32x4*>(src);
+      const unsigned in[4] = {w[0], w[1], w[2], w[3]};
+      unsigned codes[2];
+      e4m3_codes8(in, inv, codes);
       u32x2 o;
-#pragma unroll
-      for (int e = 0; e < 2; ++e) {
-        o[e] = e4m3_code(bf16_lo(w[2 * e]), inv) | (e4m3_code(bf16_hi(w[2 * e]), inv) << 8) |
-               (e4m3_code(bf16_lo(w[2 * e + 1]), inv) << 16) | (e4m3_code(bf16_hi(w[2 * e + 1]), inv) << 24);
-      }
+      o[0] = codes[0];
+      o[1] = codes[1];
       *reinterpret_cast<u32x2*>(dst) = o;
     }
   }
