@@ -30,9 +30,12 @@ __global__ __launch_bounds__(kCompactThreads) void compact_rows_kernel(
     count = c < count ? (c < 0 ? 0 : c) : count;
   }
   // rows [0, count) are gathered through ids; rows [count, count + tail.rows) are the tail's rows in order (the
-  // chunk that a rollout appends behind the retained rows, Alg. 2)
+  // chunk that a rollout appends behind the retained rows, Alg. 2).  The tail rows are handed out first: quantising
+  // one is a long chain of integer arithmetic, which then runs beside the other waves' memory-bound gathers instead
+  // of trailing behind them.
   const int total = count + tail.rows;
-  for (int r = wave; r < total; r += n_waves) {
+  for (int w = wave; w < total; w += n_waves) {
+    const int r = w < tail.rows ? count + w : w - tail.rows;
     const u32x4 *ks, *vs;
     int id = 0;
     if (r < count) {
