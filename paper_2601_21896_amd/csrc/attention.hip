@@ -146,11 +146,14 @@ __device__ __forceinline__ bf16x8 lds_read_vt(const lds_byte* p, int row_bytes8)
 // (masked elements of s_cur set to -inf beforehand, p_prev = 0 before the first tile, a clamped K tile when
 // there is no next tile), so this is the only implementation of the step.
 // s_*[kb] = key block kb (32 keys) of the tile; p_*[ks] = 16-key slice ks of the tile.
-template <int D>
+// issue_k / issue_v start this step's global -> LDS tile copies.  They are called a few slots into the step, not at
+// its start: right after the barrier all eight waves would queue their copies at once and sit behind the memory pipe
+// (a wave issues nothing while its copy waits), whereas an eighth and a half of the way in they find it free.
+template <int D, typename IssueK, typename IssueV>
 __device__ __forceinline__ void attn_step(const f32x16 (&s_cur)[2], f32x16 (&s_nxt)[2], const u32x4 (&p_prev)[4],
                                           u32x4 (&p_cur)[4], f32x16 (&o)[D / 32], const bf16x8 (&qf)[D / 16],
                                           float& msc, float& l_run, const lds_byte* k_tile, const lds_byte* v_tile,
-                                          int kx2, int vx2, float sc) {
+                                          int kx2, int vx2, float sc, IssueK&& issue_k, IssueV&& issue_v) {
   constexpr int ROWB = 2 * D;
   constexpr int KD = D / 16;
   constexpr int DB = D / 32;
@@ -158,6 +161,7 @@ __device__ __forceinline__ void attn_step(const f32x16 (&s_cur)[2], f32x16 (&s_n
   constexpr int NP = 4 * DB;       // MFMAs of the O^T update: 4 key slices x DB row blocks
   constexpr int NSLOT = NS + NP;   // MFMAs per step (NS == NP for D = 64 and 128)
   constexpr int A_SLOTS = 5;       // slots that carry the max / threshold work
+  constexpr int K_ISSUE = NSLOT / 8, V_ISSUE = NSLOT / 2;  // slots behind which the tile copies are started
   static_assert(NS == NP, "the slot pattern alternates one MFMA of each product");
   float alpha, mx, msc_new, psum = 0.f, q0 = 0.f, q1 = 0.f;
   bool grow;
@@ -252,6 +256,14 @@ __device__ __forceinline__ void attn_step(const f32x16 (&s_cur)[2], f32x16 (&s_n
       }
     }
     __builtin_amdgcn_sched_barrier(0);
+    if (i == K_ISSUE) {
+      issue_k();
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (i == V_ISSUE) {
+      issue_v();
+      __builtin_amdgcn_sched_barrier(0);
+    }
   }
   if (!kAblateSoftmax) {  // the last unit
     psum += q0;
@@ -535,13 +547,17 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnArgs
         }
       }
     };
-    // Step t (relative to the segment) reads K tile tb+t+1 and V tile tb+t-1.  At its start K(t+S) and V(t+S-2) are
+    // Step t (relative to the segment) reads K tile tb+t+1 and V tile tb+t-1.  During it K(t+S) and V(t+S-2) are
     // issued into the slots of K(t) and V(t-2), whose last readers finished in step t-1.  Tiles past the end of the
     // key axis hold clamped rows and are masked or never read.
     // In the gather variant the ids of tiles kt and kt-2 must already be visible in the ids ring.
-    auto issue_tiles = [&](int kt) {  // kt relative to the segment
-      issue_one(tb + kt, p.Kc, p.Kn, k_land, k_offc, k_offn, false);
+    auto issue_k_tile = [&](int kt) { issue_one(tb + kt, p.Kc, p.Kn, k_land, k_offc, k_offn, false); };
+    auto issue_v_tile = [&](int kt) {
       if (kt >= 2) issue_one(tb + kt - 2, p.Vc, p.Vn, v_land, v_offc, v_offn, true);
+    };
+    auto issue_tiles = [&](int kt) {  // kt relative to the segment
+      issue_k_tile(kt);
+      issue_v_tile(kt);
     };
     auto k_addr = [&](int t) { return k_ring + ((tb + t) % CK) * TILEB + k_off; };
     auto v_addr = [&](int t) { return v_ring + ((tb + t) % CK) * TILEB + v_off; };
@@ -661,10 +677,11 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnArgs
         {
           const int t = 2 * T;
           if (GATHER) issue_ids(tb + t + kAtStages + kAtIdLead);
-          if (!kAblateLoads) issue_tiles(t + LEAD);
           if (KV8) cook_step(t, 2 * n_iter);
           if ((tb + t + 1) * kAtTileKeys > lim_min) attn_mask(s_a, (tb + t) * kAtTileKeys, lim, g);
-          attn_step<D>(s_a, s_b, p_b, p_a, o, qf, msc, l_run, k_addr(t + 1), v_addr(t > 0 ? t - 1 : 0), kx2, vx2, sc);
+          attn_step<D>(
+              s_a, s_b, p_b, p_a, o, qf, msc, l_run, k_addr(t + 1), v_addr(t > 0 ? t - 1 : 0), kx2, vx2, sc,
+              [&] { if (!kAblateLoads) issue_k_tile(t + LEAD); }, [&] { if (!kAblateLoads) issue_v_tile(t + LEAD); });
           if (KV8) __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): this step's bf16 rows are written
           wait_vmcnt<(kAtStages - 2) * (2 * LPT + (GATHER ? 1 : 0))>();
           __builtin_amdgcn_s_barrier();
@@ -672,10 +689,11 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnArgs
         {
           const int t = 2 * T + 1;
           if (GATHER) issue_ids(tb + t + kAtStages + kAtIdLead);
-          if (!kAblateLoads) issue_tiles(t + LEAD);
           if (KV8) cook_step(t, 2 * n_iter);
           if ((tb + t + 1) * kAtTileKeys > lim_min) attn_mask(s_b, (tb + t) * kAtTileKeys, lim, g);
-          attn_step<D>(s_b, s_a, p_a, p_b, o, qf, msc, l_run, k_addr(T + 1 < n_iter ? t + 1 : t), v_addr(t - 1), kx2, vx2, sc);
+          attn_step<D>(
+              s_b, s_a, p_a, p_b, o, qf, msc, l_run, k_addr(T + 1 < n_iter ? t + 1 : t), v_addr(t - 1), kx2, vx2, sc,
+              [&] { if (!kAblateLoads) issue_k_tile(t + LEAD); }, [&] { if (!kAblateLoads) issue_v_tile(t + LEAD); });
           if (KV8) __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
           wait_vmcnt<(kAtStages - 2) * (2 * LPT + (GATHER ? 1 : 0))>();
           __builtin_amdgcn_s_barrier();
