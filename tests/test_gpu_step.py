@@ -207,6 +207,14 @@ def test_rollout_row_sizes_on_both_sides_of_the_fused_append(N, D):
     assert sizes == [24, 48, 72, 84, 84, 84]
 
 
+def test_rollout_with_zero_budget_keeps_only_the_chunk():
+    # k = 0: every step evicts the whole cache (the selection that rides in the scoring launch writes no index, the
+    # compaction launch has no row to gather and only appends the chunk), attention sees the chunk alone
+    cfg = wl.scaled(wl.C1, frame_tokens=30, chunk_frames=3, cache_frames=0, k=0)     # Lc = 90
+    out, sizes = _rollout(cfg, 0, 4, cfg.Lc)
+    assert sizes == [90, 90, 90, 90]
+
+
 def test_rollout_with_frame_sink_keeps_the_first_frame():
     cfg = wl.scaled(wl.C1, frame_tokens=30, chunk_frames=3, cache_frames=0, k=240)     # Lc = 90
     first = wl.round_to_bf16(wl.make_chunk_inputs(cfg, 0)["K_chunk"])[:30]
