@@ -376,6 +376,12 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnArgs
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // said to be uniform: what depends on it stays scalar
+  // Query block of this wave inside the 256-query tile.  Waves w and w + 4 share a SIMD; they take neighbouring blocks,
+  // so that a ragged tile (the last one of a head: 72 of 256 rows at the Wan-1.3B shape) fills SIMDs pairwise and
+  // steps at the pace of the full tiles.  With block = wave its few busy waves would each have a SIMD to themselves,
+  // run through the keys twice as fast as the other workgroups of the head and pull every K/V line into the L2 long
+  // before they need it, i.e. once more from HBM.
+  const int qblk = 2 * (wave & 3) + (wave >> 2);
   const int g = lane >> 5, c = lane & 31;
   // Logical workgroup.  Workgroups are handed to the 8 XCDs round-robin in launch order and every XCD has its own
   // L2, so XCD x (workgroups x, x + 8, ...) takes one contiguous range of the head-major work list: at any time an
@@ -471,7 +477,7 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnArgs
       return p.n_kept + (int)(e < p.Lc ? e : p.Lc);
     };
     const int key_end = 2 * pb * kAtTileKeys;
-    const int q_row = i_first + wave * 32 + c;
+    const int q_row = i_first + qblk * 32 + c;
     const int lim_q = visible(q_row < p.Lq ? q_row : p.Lq - 1);
     const int lim = lim_q < key_end ? lim_q : key_end;
     const int lim_first = visible(i_first);
@@ -620,7 +626,7 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnArgs
 
     // A wave whose 32 queries all lie past the end (the last query tile of a head is usually ragged) still loads its
     // share of every tile and joins every barrier, but does no arithmetic: on this chip energy is time.
-    if (__builtin_amdgcn_readfirstlane(i_first + wave * 32) >= p.Lq) {
+    if (__builtin_amdgcn_readfirstlane(i_first + qblk * 32) >= p.Lq) {
       __builtin_amdgcn_s_barrier();  // the one after the other waves' first product
 #pragma unroll 1
       for (int t = 0; t < 2 * n_iter; ++t) {
@@ -734,7 +740,7 @@ __global__ __launch_bounds__(kAtThreads, 1) void chunk_attention_kernel(AttnArgs
         }
       } else if (q_row < p.Lq) {  // partial result of this segment, for attn_combine_kernel
         const int pslot = 2 * wg + (first_segment ? 0 : 1);
-        const int ql = wave * 32 + c;
+        const int ql = qblk * 32 + c;
         float* po = wk.part_o + ((long long)pslot * kAtBQ + ql) * D;
 #pragma unroll
         for (int b = 0; b < DB; ++b)
