@@ -34,8 +34,8 @@ TOL = {"score_max_abs": 1e-3, "attn_max_abs": 2e-2, "attn_rel_fro": 5e-3}   # th
 # HBM bytes per attention launch from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE, scaled by a copy kernel): a figure
 # from a separate counter run whose summary is tracked under profiles/, NOT re-measured by this run.
 ATTENTION_TRAFFIC = {
-    # profiles/step_C1_hbm_traffic_pmc.md: 146900 KiB x 1.98 fetched + 14040 KiB written
-    ("C1", True): (int((146900 * 1.98 + 14040) * 1024), "profiles/step_C1_hbm_traffic_pmc.md"),
+    # profiles/step_C1_hbm_traffic_pmc.md: 107200 KiB x 1.98 fetched + 14040 KiB written
+    ("C1", True): (int((107200 * 1.98 + 14040) * 1024), "profiles/step_C1_hbm_traffic_pmc.md"),
 }
 
 
