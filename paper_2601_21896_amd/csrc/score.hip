@@ -12,6 +12,8 @@
 //  - score_stream_kernel (M a multiple of 256): the measured path.  W1 and the features both stream
 //    global -> LDS through a ring of 64-feature slabs; a workgroup owns several 32-token tiles so that one W1
 //    fragment feeds several matrix instructions.  Described in detail above the kernel.
+//    In a rollout step one extra workgroup of this launch runs the top-k selection on the stored score list
+//    (select_body.h), which does not depend on the chunk's scores (Alg. 2: Top-k before the chunk is appended).
 //  - score_mfma_kernel (other M a multiple of 32): a wave owns 32 tokens and loads their feature rows straight
 //    into B-operand registers; W1 is staged through LDS in 64-feature slabs shared by the waves of a workgroup.
 //

@@ -12,6 +12,7 @@
 // words; a radix-2 pass is then two instructions per word (and + popcount) plus one block-wide sum, and
 // the "greater" and "equal" masks the emit needs fall out of the 32 passes.  Longer lists fall back to
 // four 8-bit passes with LDS histograms that re-read the list from L2.
+// The bit-sliced device code lives in select_body.h (the scoring kernel of a rollout step carries it along).
 #include "pafu_internal.h"
 #include "select_body.h"
 
