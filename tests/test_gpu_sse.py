@@ -2,7 +2,12 @@
 
 Tolerance: the kernel computes q.k with fp32 accumulation of exact bf16 products (error ~1e-6 relative to |z| <= ~30
 in the exponent), the exponential and the logarithm with the hardware's base-2 units (~1 ulp) and sums L terms in
-fp32: the weights come out within ~1e-4 relative.  The test allows 1e-3 relative plus 1e-9 absolute."""
+fp32: the weights come out within ~1e-4 relative.  The test allows 1e-3 relative plus 1e-9 absolute (this
+repository's own bound: the paper states none for this score).
+
+Oracle parity runs up to L = 4680 (three frames).  At the teacher shape (L = 32760, 12 heads) the oracle would hold an
+8.6 GB weight matrix per head, so that shape is covered by two closed forms only (uniform attention, periodic keys):
+they pin the normalisation, the block partition and the indexing at full size, not general values."""
 import math
 
 import numpy as np
